@@ -1,0 +1,195 @@
+/*
+ * CPU oracle for Hybrid Target Attention (HTA) with grouped-query heads.  TEST INFRASTRUCTURE ONLY:
+ * it exists to check the GPU library and is never part of the product path.  It shares no code
+ * with the HIP kernels and is deliberately plain: float64 throughout, one loop per index, the
+ * mask evaluated per (query token, key token) from the token types, no tiling, no online
+ * softmax, no skipping.
+ *
+ * What it computes (Section 3.2.2):
+ *   full attention layer    A^(h)   = phi2(Q^(h)   K^(g)T (.) M  ) V^(g)     every token is a query
+ *   target attention layer  A_T^(h) = phi2(Q_T^(h) K^(g)T (.) M_T) V^(g)     queries = T-tokens only,
+ *                           M_T = the T-token rows of M, K/V from all tokens
+ *   g = ceil(h / r) for 1-based h, r = H / G (grouped-query attention): with 0-based heads, g = h / r.
+ *   Dynamic mask M, rules 1 and 3: history tokens are visible to every token; a target token is
+ *   visible only to itself.  (Rule 2, the timestamp rule for real-time tokens, is not part of
+ *   this path: a user's sample here is history tokens followed by target tokens.)
+ *
+ * Readings where the paper is silent (kept identical in the GPU library):
+ *   - phi2 is a row softmax over the visible keys; masked keys are excluded (weight exactly 0).
+ *   - "X visible to Y" means query Y may attend to key X; rows of M are queries.
+ *   - logits are scaled by an explicit softmax_scale argument.
+ *   - lse is the natural-log logsumexp of the scaled visible logits.
+ *
+ * Layout: q/out/dout/dq are [total_q][Hq][d]; k/v/dk/dv are [total_kv][Hkv][d]; lse is [Hq][total_q].
+ * Per user b the K/V rows are L_b history tokens then T_b target tokens, starting at kv_start[b].
+ * Query rows start at q_start[b]: N_b = L_b + T_b rows in a full layer, T_b rows in a target layer.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { TOKEN_HISTORY = 0, TOKEN_TARGET = 1 };
+enum { LAYER_FULL = 0, LAYER_TARGET = 1 };
+
+/* type of token number `tok` (0-based within the user's sample) */
+static int token_type(int64_t tok, int64_t hist_len) { return tok < hist_len ? TOKEN_HISTORY : TOKEN_TARGET; }
+
+/* dynamic mask entry M[query token][key token] */
+static int visible(int64_t query_tok, int64_t key_tok, int64_t hist_len) {
+    if (token_type(key_tok, hist_len) == TOKEN_HISTORY) return 1; /* rule 1 */
+    return key_tok == query_tok;                                   /* rule 3 */
+}
+
+int hta_oracle_num_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* Forward.  Returns 0, or -1 on bad scalar arguments. */
+int hta_oracle_fwd(const double* q, const double* k, const double* v, double* out, double* lse,
+                   const int32_t* q_start, const int32_t* kv_start, const int32_t* hist_len,
+                   const int32_t* n_targets, int32_t batch, int64_t total_q, int32_t Hq, int32_t Hkv,
+                   int32_t d, double scale, int32_t layer) {
+    if (Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0 || d <= 0 || batch < 0) return -1;
+    if (layer != LAYER_FULL && layer != LAYER_TARGET) return -1;
+    const int r = Hq / Hkv;
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int b = 0; b < batch; b++) {
+        for (int h = 0; h < Hq; h++) {
+            const int g = h / r;
+            const int64_t L = hist_len[b], T = n_targets[b], N = L + T;
+            const int64_t first_tok = (layer == LAYER_FULL) ? 0 : L; /* token of query row 0 */
+            const int64_t n_rows = N - first_tok;
+            double* s = (double*)malloc((size_t)(N > 0 ? N : 1) * sizeof(double));
+            for (int64_t row = 0; row < n_rows; row++) {
+                const int64_t i = first_tok + row; /* query token */
+                const double* qi = q + ((int64_t)(q_start[b] + row) * Hq + h) * d;
+                double smax = -INFINITY;
+                for (int64_t j = 0; j < N; j++) {
+                    if (!visible(i, j, L)) continue;
+                    const double* kj = k + ((int64_t)(kv_start[b] + j) * Hkv + g) * d;
+                    double dot = 0.0;
+                    for (int c = 0; c < d; c++) dot += qi[c] * kj[c];
+                    s[j] = scale * dot;
+                    if (s[j] > smax) smax = s[j];
+                }
+                double denom = 0.0;
+                for (int64_t j = 0; j < N; j++)
+                    if (visible(i, j, L)) denom += exp(s[j] - smax);
+                const double lse_i = smax + log(denom);
+                double* oi = out + ((int64_t)(q_start[b] + row) * Hq + h) * d;
+                for (int c = 0; c < d; c++) oi[c] = 0.0;
+                for (int64_t j = 0; j < N; j++) {
+                    if (!visible(i, j, L)) continue;
+                    const double p = exp(s[j] - lse_i);
+                    const double* vj = v + ((int64_t)(kv_start[b] + j) * Hkv + g) * d;
+                    for (int c = 0; c < d; c++) oi[c] += p * vj[c];
+                }
+                lse[(int64_t)h * total_q + q_start[b] + row] = lse_i;
+            }
+            free(s);
+        }
+    }
+    return 0;
+}
+
+/*
+ * Backward of the forward above for an upstream gradient dout (softmax Jacobian written out):
+ *   p_ij  = exp(s_ij - lse_i)            delta_i = <dout_i, out_i>
+ *   dp_ij = <dout_i, v_j>                ds_ij   = p_ij (dp_ij - delta_i)
+ *   dq_i  = scale sum_j ds_ij k_j        dk_j = scale sum_{h in g} sum_i ds_ij q_i
+ *   dv_j  = sum_{h in g} sum_i p_ij dout_i
+ * dq, dk, dv are fully overwritten.  `out` and `lse` must come from hta_oracle_fwd on the same inputs.
+ */
+int hta_oracle_bwd(const double* dout, const double* q, const double* k, const double* v,
+                   const double* out, const double* lse, double* dq, double* dk, double* dv,
+                   const int32_t* q_start, const int32_t* kv_start, const int32_t* hist_len,
+                   const int32_t* n_targets, int32_t batch, int64_t total_q, int32_t Hq, int32_t Hkv,
+                   int32_t d, double scale, int32_t layer) {
+    if (Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0 || d <= 0 || batch < 0) return -1;
+    if (layer != LAYER_FULL && layer != LAYER_TARGET) return -1;
+    const int r = Hq / Hkv;
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int b = 0; b < batch; b++) {
+        for (int g = 0; g < Hkv; g++) { /* one thread owns all of dk/dv[b, :, g, :] */
+            const int64_t L = hist_len[b], T = n_targets[b], N = L + T;
+            const int64_t first_tok = (layer == LAYER_FULL) ? 0 : L;
+            const int64_t n_rows = N - first_tok;
+            for (int64_t j = 0; j < N; j++) {
+                double* dkj = dk + ((int64_t)(kv_start[b] + j) * Hkv + g) * d;
+                double* dvj = dv + ((int64_t)(kv_start[b] + j) * Hkv + g) * d;
+                for (int c = 0; c < d; c++) dkj[c] = dvj[c] = 0.0;
+            }
+            for (int h = g * r; h < (g + 1) * r; h++) {
+                for (int64_t row = 0; row < n_rows; row++) {
+                    const int64_t i = first_tok + row;
+                    const int64_t qrow = (int64_t)(q_start[b] + row) * Hq + h;
+                    const double* qi = q + qrow * d;
+                    const double* doi = dout + qrow * d;
+                    const double* oi = out + qrow * d;
+                    double* dqi = dq + qrow * d;
+                    const double lse_i = lse[(int64_t)h * total_q + q_start[b] + row];
+                    double delta = 0.0;
+                    for (int c = 0; c < d; c++) delta += doi[c] * oi[c];
+                    for (int c = 0; c < d; c++) dqi[c] = 0.0;
+                    for (int64_t j = 0; j < N; j++) {
+                        if (!visible(i, j, L)) continue;
+                        const int64_t kvrow = (int64_t)(kv_start[b] + j) * Hkv + g;
+                        const double* kj = k + kvrow * d;
+                        const double* vj = v + kvrow * d;
+                        double dot = 0.0, dp = 0.0;
+                        for (int c = 0; c < d; c++) { dot += qi[c] * kj[c]; dp += doi[c] * vj[c]; }
+                        const double p = exp(scale * dot - lse_i);
+                        const double ds = p * (dp - delta);
+                        double* dkj = dk + kvrow * d;
+                        double* dvj = dv + kvrow * d;
+                        for (int c = 0; c < d; c++) {
+                            dqi[c] += scale * ds * kj[c];
+                            dkj[c] += scale * ds * qi[c];
+                            dvj[c] += p * doi[c];
+                        }
+                    }
+                }
+            }
+        }
+    }
+    return 0;
+}
+
+/* Attention probabilities of one (user, head) as a dense [n_rows][N] matrix (0 where masked):
+ * lets tests check that rows sum to one and inspect which pairs carry weight. */
+int hta_oracle_probs(const double* q, const double* k, double* probs, int32_t q_start, int32_t kv_start,
+                     int32_t hist_len, int32_t n_targets, int32_t head, int32_t Hq, int32_t Hkv, int32_t d,
+                     double scale, int32_t layer) {
+    if (Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0 || d <= 0 || head < 0 || head >= Hq) return -1;
+    const int r = Hq / Hkv, g = head / r;
+    const int64_t L = hist_len, N = (int64_t)hist_len + n_targets;
+    const int64_t first_tok = (layer == LAYER_FULL) ? 0 : L;
+    for (int64_t row = 0; row < N - first_tok; row++) {
+        const int64_t i = first_tok + row;
+        const double* qi = q + ((int64_t)(q_start + row) * Hq + head) * d;
+        double* pr = probs + row * N;
+        double smax = -INFINITY;
+        for (int64_t j = 0; j < N; j++) {
+            pr[j] = 0.0;
+            if (!visible(i, j, L)) continue;
+            const double* kj = k + ((int64_t)(kv_start + j) * Hkv + g) * d;
+            double dot = 0.0;
+            for (int c = 0; c < d; c++) dot += qi[c] * kj[c];
+            pr[j] = scale * dot;
+            if (pr[j] > smax) smax = pr[j];
+        }
+        double denom = 0.0;
+        for (int64_t j = 0; j < N; j++)
+            if (visible(i, j, L)) denom += exp(pr[j] - smax);
+        for (int64_t j = 0; j < N; j++) pr[j] = visible(i, j, L) ? exp(pr[j] - smax) / denom : 0.0;
+    }
+    return 0;
+}

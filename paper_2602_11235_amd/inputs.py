@@ -1,0 +1,245 @@
+"""Seeded synthetic inputs for Hybrid Target Attention (HTA).
+
+This module only *draws* data: jagged lengths and q/k/v/dout values.  It holds none of the
+attention arithmetic, so both the CPU oracle's tests and the HIP path's tests can consume the
+very same bits from it.
+
+Workload structure (Section 3.2.1, token order X = (H; R; T)): every aggregated user sample is
+one history segment of ``L_b`` tokens followed by ``T_b`` target tokens; lengths vary per user,
+so a batch is packed ("jagged") with prefix-sum offsets instead of padding.
+
+Random numbers come from a counter-based generator (the splitmix64 sequence, one independent
+stream per tensor) followed by a Box-Muller transform in float64, so the values depend only on
+(seed, stream, index) and not on any library's generator.
+"""
+from __future__ import annotations
+
+import dataclasses
+import math
+from typing import Dict, Optional
+
+import numpy as np
+
+LAYER_FULL = 0     # queries = every token of the user (full attention layer, Eq. for A^(l,h))
+LAYER_TARGET = 1   # queries = target tokens only (target attention layer, Eq. for A_T^(l,h))
+
+_GOLDEN = np.uint64(0x9E3779B97F4A7C15)
+_M1 = np.uint64(0xBF58476D1CE4E5B9)
+_M2 = np.uint64(0x94D049BB133111EB)
+
+
+def _mix(z: np.ndarray) -> np.ndarray:
+    z = (z ^ (z >> np.uint64(30))) * _M1
+    z = (z ^ (z >> np.uint64(27))) * _M2
+    return z ^ (z >> np.uint64(31))
+
+
+def stream_key(seed: int, stream: int) -> np.uint64:
+    """Key of an independent stream: two rounds of the splitmix64 finaliser over (seed, stream)."""
+    with np.errstate(over="ignore"):
+        a = _mix(np.asarray([np.uint64(seed) * _GOLDEN + np.uint64(stream + 1)], dtype=np.uint64))
+        a = _mix(a + _GOLDEN)
+    return a[0]
+
+
+def raw_bits(key: np.uint64, start: int, n: int) -> np.ndarray:
+    """splitmix64 outputs number start .. start+n-1 of the sequence whose state begins at ``key``."""
+    with np.errstate(over="ignore"):
+        ctr = np.arange(start + 1, start + n + 1, dtype=np.uint64)
+        return _mix(key + ctr * _GOLDEN)
+
+
+def uniform01(key: np.uint64, start: int, n: int) -> np.ndarray:
+    """float64 uniforms in (0, 1): the top 53 bits, shifted by half a unit so 0 never occurs."""
+    return ((raw_bits(key, start, n) >> np.uint64(11)).astype(np.float64) + 0.5) * (1.0 / 9007199254740992.0)
+
+
+def normal(key: np.uint64, n: int, chunk: int = 1 << 22) -> np.ndarray:
+    """n standard normals (float64) by Box-Muller; element 2i and 2i+1 come from uniform pair i."""
+    out = np.empty(n, dtype=np.float64)
+    pos = 0
+    while pos < n:
+        m = min(chunk, n - pos)
+        first_pair = pos // 2
+        npairs = (pos + m + 1) // 2 - first_pair
+        u = uniform01(key, 2 * first_pair, 2 * npairs)
+        r = np.sqrt(-2.0 * np.log(u[0::2]))
+        t = (2.0 * math.pi) * u[1::2]
+        z = np.empty(2 * npairs, dtype=np.float64)
+        z[0::2] = r * np.cos(t)
+        z[1::2] = r * np.sin(t)
+        off = pos - 2 * first_pair
+        out[pos:pos + m] = z[off:off + m]
+        pos += m
+    return out
+
+
+# ----------------------------------------------------------------------------- bf16 containers
+def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """Round-to-nearest-even float32 -> bfloat16, returned as uint16 bit patterns (finite inputs)."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    rounded = (u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))) >> np.uint32(16)
+    return rounded.astype(np.uint16)
+
+
+def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+# ----------------------------------------------------------------------------- workload recipes
+@dataclasses.dataclass(frozen=True)
+class Config:
+    """One synthetic workload.  hist/targets are ('fixed', n) | ('list', [...]) | ('uniform', lo, hi)
+    | ('pareto', scale, cap) with L = min(cap, floor(scale / u)), u ~ U(0,1)."""
+    name: str
+    layer: int
+    batch: int
+    hist: tuple
+    targets: tuple
+    Hq: int
+    Hkv: int
+    head_dim: int
+    dtype: str          # 'bf16' | 'fp32'
+    std: float          # q, k, v ~ std * N(0, 1)
+    seed: int
+    dout_std: float = 1.0
+
+
+CONFIGS: Dict[str, Config] = {
+    # The five benchmark/parity workloads.  C3 is the one the headline metric is quoted on.
+    "C1": Config("C1", LAYER_FULL, 2, ("list", [40, 64]), ("fixed", 8), 4, 1, 16, "fp32", 0.5, 0),
+    "C2": Config("C2", LAYER_FULL, 64, ("uniform", 128, 512), ("fixed", 32), 8, 2, 64, "bf16", 0.3, 1),
+    "C3": Config("C3", LAYER_FULL, 256, ("uniform", 512, 1024), ("fixed", 64), 8, 2, 64, "bf16", 0.3, 2),
+    "C3_1024": Config("C3_1024", LAYER_FULL, 256, ("fixed", 1024), ("fixed", 64), 8, 2, 64, "bf16", 0.3, 2),
+    "C4": Config("C4", LAYER_TARGET, 512, ("fixed", 2048), ("fixed", 128), 16, 4, 64, "bf16", 0.3, 3),
+    "C5": Config("C5", LAYER_FULL, 128, ("pareto", 750.0, 8192), ("uniform", 16, 256), 16, 2, 128, "bf16", 0.3, 4),
+}
+
+# stream ids (fixed; part of the recipe)
+_S_HIST, _S_TGT, _S_Q, _S_K, _S_V, _S_DO = 0, 1, 2, 3, 4, 5
+
+
+def _draw_lengths(spec: tuple, key: np.uint64, batch: int) -> np.ndarray:
+    kind = spec[0]
+    if kind == "fixed":
+        return np.full(batch, int(spec[1]), dtype=np.int32)
+    if kind == "list":
+        vals = np.asarray(spec[1], dtype=np.int32)
+        assert vals.shape[0] == batch
+        return vals.copy()
+    u = uniform01(key, 0, batch)
+    if kind == "uniform":
+        lo, hi = int(spec[1]), int(spec[2])
+        return (lo + np.floor(u * (hi - lo + 1)).astype(np.int64)).clip(lo, hi).astype(np.int32)
+    if kind == "pareto":
+        scale, cap = float(spec[1]), int(spec[2])
+        return np.minimum(cap, np.floor(scale / u)).astype(np.int32)
+    raise ValueError(f"unknown length spec {spec!r}")
+
+
+@dataclasses.dataclass
+class Case:
+    """A packed jagged batch.  q/k/v/dout hold float32 values exactly representable in ``dtype``
+    (for bf16 the *_bits arrays carry the uint16 patterns the device receives)."""
+    cfg: Config
+    hist_len: np.ndarray       # [B] int32
+    n_targets: np.ndarray      # [B] int32
+    kv_offsets: np.ndarray     # [B+1] int32, prefix sums of L_b + T_b
+    q_offsets: np.ndarray      # [B+1] int32, == kv_offsets (FULL) or prefix sums of T_b (TARGET)
+    q: np.ndarray              # [total_q, Hq, d]  float32
+    k: np.ndarray              # [total_kv, Hkv, d] float32
+    v: np.ndarray              # [total_kv, Hkv, d] float32
+    dout: Optional[np.ndarray]  # [total_q, Hq, d] float32 or None
+    scale: float
+
+    @property
+    def total_q(self) -> int:
+        return int(self.q_offsets[-1])
+
+    @property
+    def total_kv(self) -> int:
+        return int(self.kv_offsets[-1])
+
+    @property
+    def batch(self) -> int:
+        return int(self.hist_len.shape[0])
+
+
+def _values(key: np.uint64, shape: tuple, std: float, dtype: str) -> np.ndarray:
+    n = int(np.prod(shape)) if len(shape) else 1
+    x = (normal(key, n) * std).astype(np.float32)
+    if dtype == "bf16":
+        x = bf16_bits_to_f32(f32_to_bf16_bits(x))
+    return x.reshape(shape)
+
+
+def offsets_from_lengths(lengths: np.ndarray) -> np.ndarray:
+    off = np.zeros(lengths.shape[0] + 1, dtype=np.int64)
+    np.cumsum(lengths.astype(np.int64), out=off[1:])
+    assert off[-1] < 2 ** 31
+    return off.astype(np.int32)
+
+
+def make_case(cfg: Config, with_dout: bool = True, hist_len: Optional[np.ndarray] = None,
+              n_targets: Optional[np.ndarray] = None) -> Case:
+    """Draw one batch for ``cfg``.  Order of draws: lengths (history, targets), then q, k, v, dout,
+    each tensor from its own stream in memory order.  Explicit ``hist_len`` / ``n_targets``
+    override the drawn lengths (edge-case tests)."""
+    if hist_len is None:
+        hist_len = _draw_lengths(cfg.hist, stream_key(cfg.seed, _S_HIST), cfg.batch)
+    if n_targets is None:
+        n_targets = _draw_lengths(cfg.targets, stream_key(cfg.seed, _S_TGT), cfg.batch)
+    hist_len = np.asarray(hist_len, dtype=np.int32)
+    n_targets = np.asarray(n_targets, dtype=np.int32)
+    kv_offsets = offsets_from_lengths(hist_len + n_targets)
+    q_offsets = kv_offsets.copy() if cfg.layer == LAYER_FULL else offsets_from_lengths(n_targets)
+    tq, tkv = int(q_offsets[-1]), int(kv_offsets[-1])
+    q = _values(stream_key(cfg.seed, _S_Q), (tq, cfg.Hq, cfg.head_dim), cfg.std, cfg.dtype)
+    k = _values(stream_key(cfg.seed, _S_K), (tkv, cfg.Hkv, cfg.head_dim), cfg.std, cfg.dtype)
+    v = _values(stream_key(cfg.seed, _S_V), (tkv, cfg.Hkv, cfg.head_dim), cfg.std, cfg.dtype)
+    dout = None
+    if with_dout:
+        dout = _values(stream_key(cfg.seed, _S_DO), (tq, cfg.Hq, cfg.head_dim), cfg.dout_std, cfg.dtype)
+    return Case(cfg, hist_len, n_targets, kv_offsets, q_offsets, q, k, v, dout,
+                1.0 / math.sqrt(cfg.head_dim))
+
+
+def custom_config(name: str, layer: int, hist_len, n_targets, Hq: int, Hkv: int, head_dim: int,
+                  dtype: str = "bf16", std: float = 0.3, seed: int = 1234) -> Config:
+    hist_len = list(int(x) for x in hist_len)
+    n_targets = list(int(x) for x in n_targets)
+    return Config(name, layer, len(hist_len), ("list", hist_len), ("list", n_targets), Hq, Hkv, head_dim,
+                  dtype, std, seed)
+
+
+def take_users(case: Case, users) -> Case:
+    """The sub-batch made of the listed users (rows gathered, offsets rebuilt).  Users are
+    independent samples, so a result on the sub-batch is the result for those users."""
+    users = [int(u) for u in users]
+    qrows = np.concatenate([np.arange(case.q_offsets[u], case.q_offsets[u + 1]) for u in users]) if users else np.zeros(0, np.int64)
+    kvrows = np.concatenate([np.arange(case.kv_offsets[u], case.kv_offsets[u + 1]) for u in users]) if users else np.zeros(0, np.int64)
+    hl, nt = case.hist_len[users], case.n_targets[users]
+    kvo = offsets_from_lengths(hl + nt)
+    qo = kvo.copy() if case.cfg.layer == LAYER_FULL else offsets_from_lengths(nt)
+    return Case(case.cfg, hl, nt, kvo, qo, case.q[qrows], case.k[kvrows], case.v[kvrows],
+                None if case.dout is None else case.dout[qrows], case.scale)
+
+
+def user_rows(offsets: np.ndarray, users) -> np.ndarray:
+    """Row indices (into a packed tensor) of the listed users, in the listed order."""
+    users = [int(u) for u in users]
+    if not users:
+        return np.zeros(0, dtype=np.int64)
+    return np.concatenate([np.arange(offsets[u], offsets[u + 1]) for u in users])
+
+
+def visible_pairs(hist_len: np.ndarray, n_targets: np.ndarray, Hq: int, layer: int) -> int:
+    """Number of (query, key) pairs the hybrid mask leaves visible, summed over heads: per user
+    L^2 + T*L + T for a full layer and T*L + T for a target layer (the N^2 vs N*L_T terms of the
+    complexity statement in Section 3.2.2)."""
+    L = hist_len.astype(np.int64)
+    T = n_targets.astype(np.int64)
+    per = T * L + T
+    if layer == LAYER_FULL:
+        per = per + L * L
+    return int(Hq * per.sum())
