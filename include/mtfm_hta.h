@@ -1,0 +1,137 @@
+/*
+ * mtfm_hta.h -- C ABI of libmtfm_hta.so: grouped-query Hybrid Target Attention (HTA) over jagged
+ * user-level aggregated samples, hand-written for AMD gfx950 (MI355X).
+ *
+ * The operation (Section 3.2.2, "Hybrid Target Attention Architecture"):
+ *   full attention layer    A^(h)   = phi2(Q^(h)   K^(g)T (.) M  ) V^(g)      every token of a user is a query
+ *   target attention layer  A_T^(h) = phi2(Q_T^(h) K^(g)T (.) M_T) V^(g)      queries = the user's target tokens,
+ *                                                                            M_T = those rows of M, K/V = all tokens
+ *   grouped-query heads: query head h (0-based) reads key/value head g = h / r, r = Hq / Hkv
+ *                        (the paper's g = ceil(h/r) for 1-based h): consecutive query heads share a kv head.
+ *   dynamic mask M (rules 1 and 3): history tokens are visible to every token, a target token only to
+ *   itself.  The mask is never materialised: it is a function of (hist_len, token index).
+ *   Heads are concatenated along the feature axis (A = A^1 || ... || A^H): the [token][head][d] layout.
+ * Readings fixed where the paper is silent: phi2 is a row softmax over the visible keys (masked keys get
+ * weight exactly 0); logits are multiplied by the explicit softmax_scale; lse is the natural-log
+ * logsumexp of the scaled visible logits.
+ *
+ * Data layout.  A batch holds `batch` users packed back to back, no padding.  User b owns
+ *   K/V rows  kv_offsets[b] .. kv_offsets[b+1]-1 :  hist_len[b] history tokens, then n_targets[b] target tokens
+ *             (token order X = (H; T) of Section 3.2.1), so kv_offsets[b+1]-kv_offsets[b] = hist_len[b]+n_targets[b];
+ *   Q rows    q_offsets[b] .. q_offsets[b+1]-1 :  the same tokens (full layer; q_offsets may alias kv_offsets)
+ *             or only the n_targets[b] target tokens (target layer; q_offsets = prefix sums of n_targets).
+ *   q, out, dout, dq : [total_q ][Hq ][head_dim]  row-major
+ *   k, v, dk, dv     : [total_kv][Hkv][head_dim]  row-major
+ *   lse              : [Hq][total_q] float32
+ *
+ * Pointers.  Every data pointer (q,k,v,out,lse,dout,dq,dk,dv, the four int32 arrays, workspace) is a
+ * DEVICE pointer; `stream` is a hipStream_t passed as void* (NULL = the default stream).  The caller
+ * owns all buffers.  The library never allocates or frees device memory, never copies to the host and
+ * never synchronises: a call validates its scalar arguments on the host, enqueues kernels on `stream`
+ * and returns.  Device-resident arrays are not validated (that would need a device-to-host copy);
+ * they must satisfy the layout above, and hist_len[b] <= max_hist, n_targets[b] <= max_targets.
+ *
+ * Errors.  Every entry point returning int returns an mtfm_hta_status; on a non-zero status nothing
+ * has been enqueued (except MTFM_HTA_ERR_LAUNCH, reported by the runtime after an enqueue), and
+ * mtfm_hta_last_error() describes the problem.
+ */
+#ifndef MTFM_HTA_H
+#define MTFM_HTA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* exported with default visibility; everything else in the library is hidden */
+#define MTFM_HTA_API __attribute__((visibility("default")))
+
+typedef enum {
+    MTFM_HTA_OK = 0,
+    MTFM_HTA_ERR_INVALID_ARG = -1, /* null pointer, misaligned pointer, negative size, Hq % Hkv != 0, bad enum, scale <= 0 */
+    MTFM_HTA_ERR_UNSUPPORTED = -2, /* head_dim / head-group shape this build has no kernel for */
+    MTFM_HTA_ERR_WORKSPACE = -3,   /* workspace missing or smaller than mtfm_hta_workspace_bytes() */
+    MTFM_HTA_ERR_LAUNCH = -4       /* the HIP runtime refused a launch */
+} mtfm_hta_status;
+
+/* element type of q, k, v, out, dout, dq, dk, dv */
+enum { MTFM_HTA_BF16 = 0, /* bfloat16 storage, MFMA with fp32 accumulation; head_dim in {32, 64, 128} */
+       MTFM_HTA_FP32 = 1  /* float32 storage and arithmetic (plain FMA debug path); 1 <= head_dim <= 128 */ };
+
+/* which layer of a block: queries = all tokens, or target tokens only */
+enum { MTFM_HTA_LAYER_FULL = 0, MTFM_HTA_LAYER_TARGET = 1 };
+
+/*
+ * Bytes of device workspace a call with these sizes needs (0 is possible).  Pure host arithmetic.
+ * is_bwd = 0 for mtfm_hta_fwd, 1 for mtfm_hta_bwd.  Returns (size_t)-1 for invalid arguments.
+ * The workspace must be 256-byte aligned; its contents are undefined before and after a call and it
+ * may be reused by the next call on the same stream.
+ */
+MTFM_HTA_API size_t mtfm_hta_workspace_bytes(int layer, int dtype, int is_bwd, int32_t batch, int64_t total_q,
+                                int64_t total_kv, int32_t max_hist, int32_t max_targets, int32_t Hq,
+                                int32_t Hkv, int32_t head_dim);
+
+/*
+ * Forward: out = softmax_over_visible_keys(softmax_scale * Q K^T) V per user and head, and the
+ * logsumexp of every query row (Eq. for A^(l,h) of the full layer, A_T^(l,h) of the target layer).
+ *   q           in   [total_q][Hq][head_dim]
+ *   k, v        in   [total_kv][Hkv][head_dim]
+ *   out         out  [total_q][Hq][head_dim]   fully overwritten (bf16: rounded to nearest even)
+ *   lse         out  [Hq][total_q] float32     fully overwritten
+ *   q_offsets, kv_offsets  in  [batch+1] int32; hist_len, n_targets  in  [batch] int32 (all >= 0)
+ *   total_q, total_kv      = q_offsets[batch], kv_offsets[batch] (host copies, < 2^31)
+ *   max_hist, max_targets  host-known upper bounds of hist_len[] / n_targets[] (they size the launch)
+ *   softmax_scale          > 0, finite; typically 1/sqrt(head_dim)
+ * Data pointers must be 16-byte aligned.  batch == 0 or total_q == 0 is a successful no-op.
+ */
+MTFM_HTA_API int mtfm_hta_fwd(const void* q, const void* k, const void* v, void* out, float* lse,
+                 const int32_t* q_offsets, const int32_t* kv_offsets, const int32_t* hist_len,
+                 const int32_t* n_targets, int32_t batch, int64_t total_q, int64_t total_kv,
+                 int32_t max_hist, int32_t max_targets, int32_t Hq, int32_t Hkv, int32_t head_dim,
+                 float softmax_scale, int dtype, int layer, void* workspace, size_t workspace_bytes,
+                 void* stream);
+
+/*
+ * Backward of mtfm_hta_fwd for an upstream gradient dout: the probabilities are recomputed from the
+ * saved logsumexp, p_ij = exp(scale*s_ij - lse_i), then with delta_i = <dout_i, out_i>,
+ * ds_ij = p_ij (<dout_i, v_j> - delta_i):
+ *   dq_i = scale * sum_j ds_ij k_j,   dk_j = scale * sum_{h in group} sum_i ds_ij q_i,
+ *   dv_j = sum_{h in group} sum_i p_ij dout_i        (gradient of the two attention equations above).
+ *   dout, q, out  in  [total_q][Hq][head_dim];  k, v  in  [total_kv][Hkv][head_dim];  lse  in  [Hq][total_q]
+ *   dq            out [total_q][Hq][head_dim]   fully overwritten
+ *   dk, dv        out [total_kv][Hkv][head_dim] fully overwritten (in a target layer history rows receive the
+ *                 gradient of every target query, target rows that of their own query)
+ * `out` and `lse` must be what mtfm_hta_fwd produced for the same inputs.  Remaining arguments as in
+ * mtfm_hta_fwd.  Sums across workgroups use float32 atomics, so results are reproducible to
+ * rounding, not bitwise.
+ */
+MTFM_HTA_API int mtfm_hta_bwd(const void* dout, const void* q, const void* k, const void* v, const void* out,
+                 const float* lse, void* dq, void* dk, void* dv, const int32_t* q_offsets,
+                 const int32_t* kv_offsets, const int32_t* hist_len, const int32_t* n_targets,
+                 int32_t batch, int64_t total_q, int64_t total_kv, int32_t max_hist,
+                 int32_t max_targets, int32_t Hq, int32_t Hkv, int32_t head_dim, float softmax_scale,
+                 int dtype, int layer, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Host-side check of host copies of the jagged arrays (tests and callers that have them on the host):
+ * monotone offsets, kv_offsets[b+1]-kv_offsets[b] == hist_len[b]+n_targets[b], the q_offsets rule of
+ * `layer`, bounds respected.  All pointers are HOST pointers.  Returns MTFM_HTA_OK or
+ * MTFM_HTA_ERR_INVALID_ARG (with mtfm_hta_last_error() naming the first violation).
+ */
+MTFM_HTA_API int mtfm_hta_validate_host(const int32_t* q_offsets, const int32_t* kv_offsets, const int32_t* hist_len,
+                           const int32_t* n_targets, int32_t batch, int64_t total_q, int64_t total_kv,
+                           int32_t max_hist, int32_t max_targets, int layer);
+
+/* Message for the calling thread's most recent non-OK status ("" if none).  Points to thread-local
+ * static storage owned by the library: do not free; valid until the thread's next failing call. */
+MTFM_HTA_API const char* mtfm_hta_last_error(void);
+
+/* Library version, "major.minor.patch"; static storage. */
+MTFM_HTA_API const char* mtfm_hta_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MTFM_HTA_H */

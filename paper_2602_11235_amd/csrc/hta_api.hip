@@ -1,0 +1,185 @@
+// C ABI of libmtfm_hta.so: host-side argument checks and kernel dispatch.  No allocation, no
+// host<->device copies, no synchronisation here.
+#include "../../include/mtfm_hta.h"
+#include "hta_common.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct Workspace {
+    size_t delta_off, dq_off, dk_off, dv_off, total;
+};
+
+// Layout of the caller's workspace.  Forward needs none.  Backward (bf16): delta [Hq][total_q] f32,
+// dq accumulator [total_q][Hq][d] f32, dk/dv accumulators [total_kv][Hkv][d] f32.
+// Backward (fp32): delta is computed inside the row kernel; nothing needed.
+Workspace plan_workspace(int dtype, int is_bwd, int64_t total_q, int64_t total_kv, int32_t Hq, int32_t Hkv,
+                         int32_t d) {
+    Workspace w{0, 0, 0, 0, 0};
+    if (!is_bwd || dtype == MTFM_HTA_FP32) return w;
+    size_t off = 0;
+    w.delta_off = off;
+    off += align256((size_t)total_q * Hq * sizeof(float));
+    w.dq_off = off;
+    off += align256((size_t)total_q * Hq * d * sizeof(float));
+    w.dk_off = off;
+    off += align256((size_t)total_kv * Hkv * d * sizeof(float));
+    w.dv_off = off;
+    off += align256((size_t)total_kv * Hkv * d * sizeof(float));
+    w.total = off;
+    return w;
+}
+
+int check_scalars(int layer, int dtype, int32_t batch, int64_t total_q, int64_t total_kv, int32_t max_hist,
+                  int32_t max_targets, int32_t Hq, int32_t Hkv, int32_t d) {
+    if (layer != MTFM_HTA_LAYER_FULL && layer != MTFM_HTA_LAYER_TARGET)
+        return fail(MTFM_HTA_ERR_INVALID_ARG, "layer must be MTFM_HTA_LAYER_FULL or MTFM_HTA_LAYER_TARGET, got %d", layer);
+    if (dtype != MTFM_HTA_BF16 && dtype != MTFM_HTA_FP32)
+        return fail(MTFM_HTA_ERR_INVALID_ARG, "dtype must be MTFM_HTA_BF16 or MTFM_HTA_FP32, got %d", dtype);
+    if (batch < 0 || total_q < 0 || total_kv < 0 || max_hist < 0 || max_targets < 0)
+        return fail(MTFM_HTA_ERR_INVALID_ARG, "negative size (batch %d total_q %lld total_kv %lld max_hist %d max_targets %d)",
+                    batch, (long long)total_q, (long long)total_kv, max_hist, max_targets);
+    if (total_q >= (1ll << 31) || total_kv >= (1ll << 31))
+        return fail(MTFM_HTA_ERR_INVALID_ARG, "total_q / total_kv must be below 2^31 (int32 offsets)");
+    if (batch > 65535) return fail(MTFM_HTA_ERR_UNSUPPORTED, "batch %d exceeds 65535 users per call", batch);
+    if (Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0)
+        return fail(MTFM_HTA_ERR_INVALID_ARG, "Hq (%d) must be a positive multiple of Hkv (%d)", Hq, Hkv);
+    if (Hq > 65535) return fail(MTFM_HTA_ERR_UNSUPPORTED, "Hq %d exceeds 65535", Hq);
+    if (d <= 0) return fail(MTFM_HTA_ERR_INVALID_ARG, "head_dim must be positive, got %d", d);
+    if (dtype == MTFM_HTA_FP32) {
+        if (d > 128) return fail(MTFM_HTA_ERR_UNSUPPORTED, "fp32 path supports head_dim <= 128, got %d", d);
+    } else if (!hta::bf16_supported(d, Hq, Hkv)) {
+        return fail(MTFM_HTA_ERR_UNSUPPORTED, "bf16 path supports head_dim in {32, 64, 128}, got %d", d);
+    }
+    if ((int64_t)max_hist + max_targets >= (1ll << 31))
+        return fail(MTFM_HTA_ERR_INVALID_ARG, "max_hist + max_targets overflows int32");
+    return MTFM_HTA_OK;
+}
+
+bool misaligned(const void* p) { return ((uintptr_t)p & 15u) != 0; }
+
+}  // namespace
+
+extern "C" {
+
+const char* mtfm_hta_last_error(void) { return g_err; }
+
+const char* mtfm_hta_version(void) { return "0.1.0"; }
+
+size_t mtfm_hta_workspace_bytes(int layer, int dtype, int is_bwd, int32_t batch, int64_t total_q, int64_t total_kv,
+                                int32_t max_hist, int32_t max_targets, int32_t Hq, int32_t Hkv, int32_t head_dim) {
+    if (check_scalars(layer, dtype, batch, total_q, total_kv, max_hist, max_targets, Hq, Hkv, head_dim) != MTFM_HTA_OK)
+        return (size_t)-1;
+    return plan_workspace(dtype, is_bwd, total_q, total_kv, Hq, Hkv, head_dim).total;
+}
+
+int mtfm_hta_validate_host(const int32_t* q_offsets, const int32_t* kv_offsets, const int32_t* hist_len,
+                           const int32_t* n_targets, int32_t batch, int64_t total_q, int64_t total_kv,
+                           int32_t max_hist, int32_t max_targets, int layer) {
+    if (batch < 0) return fail(MTFM_HTA_ERR_INVALID_ARG, "negative batch");
+    if (layer != MTFM_HTA_LAYER_FULL && layer != MTFM_HTA_LAYER_TARGET)
+        return fail(MTFM_HTA_ERR_INVALID_ARG, "bad layer %d", layer);
+    if (!q_offsets || !kv_offsets || (batch > 0 && (!hist_len || !n_targets)))
+        return fail(MTFM_HTA_ERR_INVALID_ARG, "null array");
+    if (q_offsets[0] != 0 || kv_offsets[0] != 0) return fail(MTFM_HTA_ERR_INVALID_ARG, "offsets must start at 0");
+    for (int32_t b = 0; b < batch; b++) {
+        const int64_t L = hist_len[b], T = n_targets[b];
+        if (L < 0 || T < 0) return fail(MTFM_HTA_ERR_INVALID_ARG, "user %d: negative length", b);
+        if (L > max_hist) return fail(MTFM_HTA_ERR_INVALID_ARG, "user %d: hist_len %lld > max_hist %d", b, (long long)L, max_hist);
+        if (T > max_targets)
+            return fail(MTFM_HTA_ERR_INVALID_ARG, "user %d: n_targets %lld > max_targets %d", b, (long long)T, max_targets);
+        if ((int64_t)kv_offsets[b + 1] - kv_offsets[b] != L + T)
+            return fail(MTFM_HTA_ERR_INVALID_ARG, "user %d: kv_offsets span != hist_len + n_targets", b);
+        const int64_t rows = layer == MTFM_HTA_LAYER_FULL ? L + T : T;
+        if ((int64_t)q_offsets[b + 1] - q_offsets[b] != rows)
+            return fail(MTFM_HTA_ERR_INVALID_ARG, "user %d: q_offsets span %d != %lld query rows", b,
+                        q_offsets[b + 1] - q_offsets[b], (long long)rows);
+    }
+    if (q_offsets[batch] != total_q) return fail(MTFM_HTA_ERR_INVALID_ARG, "q_offsets[batch] != total_q");
+    if (kv_offsets[batch] != total_kv) return fail(MTFM_HTA_ERR_INVALID_ARG, "kv_offsets[batch] != total_kv");
+    return MTFM_HTA_OK;
+}
+
+int mtfm_hta_fwd(const void* q, const void* k, const void* v, void* out, float* lse, const int32_t* q_offsets,
+                 const int32_t* kv_offsets, const int32_t* hist_len, const int32_t* n_targets, int32_t batch,
+                 int64_t total_q, int64_t total_kv, int32_t max_hist, int32_t max_targets, int32_t Hq, int32_t Hkv,
+                 int32_t head_dim, float softmax_scale, int dtype, int layer, void* workspace, size_t workspace_bytes,
+                 void* stream) {
+    int rc = check_scalars(layer, dtype, batch, total_q, total_kv, max_hist, max_targets, Hq, Hkv, head_dim);
+    if (rc != MTFM_HTA_OK) return rc;
+    if (!(softmax_scale > 0.f) || !std::isfinite(softmax_scale))
+        return fail(MTFM_HTA_ERR_INVALID_ARG, "softmax_scale must be positive and finite");
+    if (batch == 0 || total_q == 0) return MTFM_HTA_OK;
+    if (!q || !k || !v || !out || !lse || !q_offsets || !kv_offsets || !hist_len || !n_targets)
+        return fail(MTFM_HTA_ERR_INVALID_ARG, "null pointer argument");
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out))
+        return fail(MTFM_HTA_ERR_INVALID_ARG, "q, k, v, out must be 16-byte aligned");
+    (void)workspace;
+    (void)workspace_bytes;  // the forward pass needs no workspace
+    hta::Params p{};
+    p.q = q; p.k = k; p.v = v; p.out = out; p.lse = lse;
+    p.q_off = q_offsets; p.kv_off = kv_offsets; p.hist_len = hist_len; p.n_targets = n_targets;
+    p.batch = batch; p.total_q = total_q; p.total_kv = total_kv; p.max_hist = max_hist; p.max_targets = max_targets;
+    p.Hq = Hq; p.Hkv = Hkv; p.d = head_dim; p.scale = softmax_scale; p.layer = layer;
+    hipStream_t s = (hipStream_t)stream;
+    hipError_t e = dtype == MTFM_HTA_FP32 ? hta::launch_fwd_fp32(p, s) : hta::launch_fwd_bf16(p, s);
+    if (e != hipSuccess) return fail(MTFM_HTA_ERR_LAUNCH, "forward launch failed: %s", hipGetErrorString(e));
+    return MTFM_HTA_OK;
+}
+
+int mtfm_hta_bwd(const void* dout, const void* q, const void* k, const void* v, const void* out, const float* lse,
+                 void* dq, void* dk, void* dv, const int32_t* q_offsets, const int32_t* kv_offsets,
+                 const int32_t* hist_len, const int32_t* n_targets, int32_t batch, int64_t total_q, int64_t total_kv,
+                 int32_t max_hist, int32_t max_targets, int32_t Hq, int32_t Hkv, int32_t head_dim, float softmax_scale,
+                 int dtype, int layer, void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_scalars(layer, dtype, batch, total_q, total_kv, max_hist, max_targets, Hq, Hkv, head_dim);
+    if (rc != MTFM_HTA_OK) return rc;
+    if (!(softmax_scale > 0.f) || !std::isfinite(softmax_scale))
+        return fail(MTFM_HTA_ERR_INVALID_ARG, "softmax_scale must be positive and finite");
+    if (batch == 0 || total_kv == 0) return MTFM_HTA_OK;
+    if (!dout || !q || !k || !v || !out || !lse || !dq || !dk || !dv || !q_offsets || !kv_offsets || !hist_len || !n_targets)
+        return fail(MTFM_HTA_ERR_INVALID_ARG, "null pointer argument");
+    if (misaligned(dout) || misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out) || misaligned(dq) ||
+        misaligned(dk) || misaligned(dv))
+        return fail(MTFM_HTA_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
+    const Workspace w = plan_workspace(dtype, 1, total_q, total_kv, Hq, Hkv, head_dim);
+    if (w.total > 0) {
+        if (!workspace || workspace_bytes < w.total)
+            return fail(MTFM_HTA_ERR_WORKSPACE, "backward needs %zu bytes of workspace, got %zu", w.total, workspace_bytes);
+        if (((uintptr_t)workspace & 255u) != 0) return fail(MTFM_HTA_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+    }
+    hta::Params p{};
+    p.dout = dout; p.q = q; p.k = k; p.v = v; p.out = const_cast<void*>(out); p.lse = const_cast<float*>(lse);
+    p.dq = dq; p.dk = dk; p.dv = dv;
+    p.q_off = q_offsets; p.kv_off = kv_offsets; p.hist_len = hist_len; p.n_targets = n_targets;
+    p.batch = batch; p.total_q = total_q; p.total_kv = total_kv; p.max_hist = max_hist; p.max_targets = max_targets;
+    p.Hq = Hq; p.Hkv = Hkv; p.d = head_dim; p.scale = softmax_scale; p.layer = layer;
+    if (w.total > 0) {
+        char* base = (char*)workspace;
+        p.delta = (float*)(base + w.delta_off);
+        p.dq_acc = (float*)(base + w.dq_off);
+        p.dk_acc = (float*)(base + w.dk_off);
+        p.dv_acc = (float*)(base + w.dv_off);
+    }
+    hipStream_t s = (hipStream_t)stream;
+    hipError_t e = dtype == MTFM_HTA_FP32 ? hta::launch_bwd_fp32(p, s) : hta::launch_bwd_bf16(p, s);
+    if (e != hipSuccess) return fail(MTFM_HTA_ERR_LAUNCH, "backward launch failed: %s", hipGetErrorString(e));
+    return MTFM_HTA_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,279 @@
+// bf16 forward kernel of Hybrid Target Attention for gfx950: QK^T and PV on the 32x32x16 bf16 MFMA
+// with float32 accumulation, online softmax, K/V tiles staged in LDS once per key/value head and
+// shared by the query heads of the GQA group (g = h / r, Section 3.2.2).
+//
+// Block skipping from the hybrid mask (rules 1 and 3): every query row of a user attends to all
+// L_b history keys and never to another token's target key, so the only tiles ever issued are
+// (row tile) x (history key tile); the single self key of a target row is added as one extra
+// online-softmax step per row in the epilogue.  No mask is stored or loaded; only the ragged last
+// history tile needs a bound check.
+//
+// Work decomposition: one workgroup = (user, kv head, chunk of `hpb` query heads of that group,
+// tile of BM query rows).  Wave w serves head (w % hpb) of the chunk and the row group (w / hpb);
+// it keeps RB blocks of 32 query rows in registers.  S is computed transposed, S^T = K Q^T, so
+// a lane owns one query row: the row maximum and sum are reductions over the lane's own
+// registers plus one exchange with the other half of the wave, and P^T in accumulator layout is
+// directly the B operand of O^T = V^T P^T.  V stays row-major in LDS and is read through the LDS
+// transpose read.
+#include "hta_common.h"
+#include "hta_mfma.h"
+
+namespace hta {
+namespace {
+
+constexpr int BN = 64;  // keys per LDS tile
+
+template <int D>
+struct Tile {
+    static constexpr int KS = D + 8;  // K row pitch (elements): 16-byte pad keeps 16-byte row reads conflict-free
+    static constexpr int VS = D + 8;  // V row pitch
+    static constexpr int LDS_ELEMS = BN * KS + BN * VS;
+};
+
+template <int D, int RB, int NW>
+__global__ __launch_bounds__(NW * 64) void fwd_bf16_kernel(Params p, int hpb, int n_hc) {
+    constexpr int NT = NW * 64;
+    constexpr int KS = Tile<D>::KS, VS = Tile<D>::VS;
+    constexpr int CPR = D / 8;                     // 16-byte chunks per K/V row
+    constexpr int NCH = BN * CPR;                  // chunks per tile
+    constexpr int CH = (NCH + NT - 1) / NT;        // chunks per thread
+    constexpr int NKS = D / 16, NDB = D / 32, NKB = BN / 32;
+    __shared__ __attribute__((aligned(16))) __bf16 smem[Tile<D>::LDS_ELEMS];
+    __bf16* Ks = smem;
+    __bf16* Vs = smem + BN * KS;
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
+    const int b = blockIdx.z;
+    const int g = blockIdx.y / n_hc, hc = blockIdx.y % n_hc;
+    const int L = p.hist_len[b], T = p.n_targets[b];
+    const int n_rows = p.layer == 0 ? L + T : T;
+    const int BM = (NW / hpb) * RB * 32;
+    const int tile_row0 = blockIdx.x * BM;
+    if (tile_row0 >= n_rows) return;  // uniform for the whole workgroup
+    const int r = p.Hq / p.Hkv;
+    const int h = g * r + hc * hpb + wave % hpb;
+    const int wrow0 = tile_row0 + (wave / hpb) * (RB * 32);
+    const int tok_shift = p.layer == 0 ? 0 : L;  // token index of query row 0
+    const int64_t q_base = p.q_off[b], kv_base = p.kv_off[b];
+    const __bf16* qg = (const __bf16*)p.q;
+    const __bf16* kg = (const __bf16*)p.k;
+    const __bf16* vg = (const __bf16*)p.v;
+    const float c2 = p.scale * LOG2E;  // logits are handled in the log2 domain
+
+    // Q fragments (B operand of S^T = K Q^T): lane = query row, 8 consecutive d values per k-step.
+    // Rows past the end of the user are clamped to the last row; their results are never stored.
+    bf16x8 qf[RB][NKS];
+#pragma unroll
+    for (int rb = 0; rb < RB; rb++) {
+        int row = wrow0 + rb * 32 + l32;
+        row = row < n_rows ? row : n_rows - 1;
+        const __bf16* qp = qg + ((q_base + row) * p.Hq + h) * D + 8 * hf;
+#pragma unroll
+        for (int ks = 0; ks < NKS; ks++) qf[rb][ks] = *(const bf16x8*)(qp + ks * 16);
+    }
+
+    float m[RB], l[RB];
+    floatx16 O[RB][NDB];
+#pragma unroll
+    for (int rb = 0; rb < RB; rb++) {
+        m[rb] = -INFINITY;
+        l[rb] = 0.f;
+#pragma unroll
+        for (int db = 0; db < NDB; db++)
+#pragma unroll
+            for (int v = 0; v < 16; v++) O[rb][db][v] = 0.f;
+    }
+
+    const int n_kt = (L + BN - 1) / BN;
+    uint4 kreg[CH], vreg[CH];
+    auto load_tile = [&](int t) {
+#pragma unroll
+        for (int i = 0; i < CH; i++) {
+            const int c = tid + i * NT;
+            const int key = t * BN + c / CPR, dc = c % CPR;
+            kreg[i] = make_uint4(0, 0, 0, 0);
+            vreg[i] = make_uint4(0, 0, 0, 0);
+            if (c < NCH && key < L) {  // keys past the history are zero-filled (their weight is 0)
+                const int64_t off = ((kv_base + key) * p.Hkv + g) * D + dc * 8;
+                kreg[i] = *(const uint4*)(kg + off);
+                vreg[i] = *(const uint4*)(vg + off);
+            }
+        }
+    };
+    auto store_tile = [&]() {
+#pragma unroll
+        for (int i = 0; i < CH; i++) {
+            const int c = tid + i * NT;
+            if (c < NCH) {
+                const int key = c / CPR, dc = c % CPR;
+                *(uint4*)(Ks + key * KS + dc * 8) = kreg[i];
+                *(uint4*)(Vs + key * VS + dc * 8) = vreg[i];
+            }
+        }
+    };
+
+    if (n_kt > 0) load_tile(0);
+    for (int t = 0; t < n_kt; t++) {
+        __syncthreads();  // everyone is done reading the previous tile
+        store_tile();
+        __syncthreads();
+        if (t + 1 < n_kt) load_tile(t + 1);  // in flight while this tile is consumed
+
+        // S^T[key][row] = sum_d K[key][d] Q[row][d]
+        floatx16 S[RB][NKB];
+#pragma unroll
+        for (int rb = 0; rb < RB; rb++)
+#pragma unroll
+            for (int kb = 0; kb < NKB; kb++)
+#pragma unroll
+                for (int v = 0; v < 16; v++) S[rb][kb][v] = 0.f;
+#pragma unroll
+        for (int kb = 0; kb < NKB; kb++) {
+#pragma unroll
+            for (int ks = 0; ks < NKS; ks++) {
+                const bf16x8 kf = *(const bf16x8*)(Ks + (kb * 32 + l32) * KS + ks * 16 + 8 * hf);
+#pragma unroll
+                for (int rb = 0; rb < RB; rb++) S[rb][kb] = mfma32(kf, qf[rb][ks], S[rb][kb]);
+            }
+        }
+        if (t == n_kt - 1 && (L % BN) != 0) {  // ragged last history tile: keys >= L_b are not visible
+#pragma unroll
+            for (int kb = 0; kb < NKB; kb++)
+#pragma unroll
+                for (int v = 0; v < 16; v++) {
+                    const int key = t * BN + kb * 32 + 8 * (v / 4) + 4 * hf + (v % 4);
+                    if (key >= L) {
+#pragma unroll
+                        for (int rb = 0; rb < RB; rb++) S[rb][kb][v] = -INFINITY;
+                    }
+                }
+        }
+        // online softmax, one query row per lane (two lanes, 32 apart, share a row)
+        bf16x8 pf[RB][NKB][2];
+#pragma unroll
+        for (int rb = 0; rb < RB; rb++) {
+            float mx = -INFINITY;
+#pragma unroll
+            for (int kb = 0; kb < NKB; kb++)
+#pragma unroll
+                for (int v = 0; v < 16; v++) mx = fmaxf(mx, S[rb][kb][v]);
+            mx = fmaxf(mx, other_half(mx));
+            const float m_new = fmaxf(m[rb], mx * c2);
+            const float alpha = fast_exp2(m[rb] - m_new);
+            m[rb] = m_new;
+            float psum = 0.f;
+#pragma unroll
+            for (int kb = 0; kb < NKB; kb++)
+#pragma unroll
+                for (int v = 0; v < 16; v++) {
+                    const float pv = fast_exp2(fmaf(S[rb][kb][v], c2, -m_new));
+                    psum += pv;
+                    pf[rb][kb][v / 8][v % 8] = (__bf16)pv;
+                }
+            l[rb] = fmaf(l[rb], alpha, psum);
+#pragma unroll
+            for (int db = 0; db < NDB; db++)
+#pragma unroll
+                for (int v = 0; v < 16; v++) O[rb][db][v] *= alpha;
+        }
+        // O^T[d][row] += sum_key V[key][d] P^T[key][row]
+#pragma unroll
+        for (int db = 0; db < NDB; db++)
+#pragma unroll
+            for (int kb = 0; kb < NKB; kb++)
+#pragma unroll
+                for (int s2 = 0; s2 < 2; s2++) {
+                    const bf16x8 vf = lds_read_tr_8(Vs, VS, kb * 32 + 16 * s2 + 4 * hf, db * 32 + 16 * ((lane >> 4) & 1), lane);
+#pragma unroll
+                    for (int rb = 0; rb < RB; rb++) O[rb][db] = mfma32(vf, pf[rb][kb][s2], O[rb][db]);
+                }
+    }
+
+    // epilogue: self key of target rows (rule 3), normalisation, stores
+    __bf16* og = (__bf16*)p.out;
+#pragma unroll
+    for (int rb = 0; rb < RB; rb++) {
+        const int row = wrow0 + rb * 32 + l32;
+        const bool live = row < n_rows;
+        const int tok = tok_shift + row;
+        if (live && tok >= L) {
+            const int64_t off = ((kv_base + tok) * p.Hkv + g) * D;
+            const __bf16* kp = kg + off + 8 * hf;
+            float dot = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < NKS; ks++) {
+                const bf16x8 kk = *(const bf16x8*)(kp + ks * 16);
+#pragma unroll
+                for (int j = 0; j < 8; j++) dot = fmaf((float)qf[rb][ks][j], (float)kk[j], dot);
+            }
+            dot += other_half(dot);
+            const float s2 = dot * c2;
+            const float m_new = fmaxf(m[rb], s2);
+            const float alpha = fast_exp2(m[rb] - m_new);
+            const float ps = fast_exp2(s2 - m_new);
+            m[rb] = m_new;
+            l[rb] = l[rb] * alpha + (hf == 0 ? ps : 0.f);
+#pragma unroll
+            for (int db = 0; db < NDB; db++)
+#pragma unroll
+                for (int v4 = 0; v4 < 4; v4++) {
+                    const bf16x4 vv = *(const bf16x4*)(vg + off + db * 32 + 8 * v4 + 4 * hf);
+#pragma unroll
+                    for (int j = 0; j < 4; j++) O[rb][db][4 * v4 + j] = fmaf(O[rb][db][4 * v4 + j], alpha, ps * (float)vv[j]);
+                }
+        }
+        const float lt = l[rb] + other_half(l[rb]);
+        if (live) {
+            const float inv = 1.f / lt;
+            __bf16* op = og + ((q_base + row) * p.Hq + h) * D;
+#pragma unroll
+            for (int db = 0; db < NDB; db++)
+#pragma unroll
+                for (int v4 = 0; v4 < 4; v4++) {
+                    bf16x4 o4;
+#pragma unroll
+                    for (int j = 0; j < 4; j++) o4[j] = (__bf16)(O[rb][db][4 * v4 + j] * inv);
+                    *(bf16x4*)(op + db * 32 + 8 * v4 + 4 * hf) = o4;
+                }
+            if (hf == 0) p.lse[(int64_t)h * p.total_q + q_base + row] = (m[rb] + __builtin_amdgcn_logf(lt)) * LN2;
+        }
+    }
+}
+
+int gcd(int a, int b) { return b == 0 ? a : gcd(b, a % b); }
+
+template <int D, int RB, int NW>
+hipError_t launch(const Params& p, hipStream_t s) {
+    const int r = p.Hq / p.Hkv;
+    const int hpb = gcd(r, NW);
+    const int n_hc = r / hpb;
+    const int BM = (NW / hpb) * RB * 32;
+    const int64_t rows = max_query_rows(p);
+    if (rows <= 0) return hipSuccess;
+    const int64_t n_rt = (rows + BM - 1) / BM;
+    if ((int64_t)p.Hkv * n_hc > 65535) return hipErrorInvalidValue;
+    dim3 grid((unsigned)n_rt, (unsigned)(p.Hkv * n_hc), (unsigned)p.batch);
+    hipLaunchKernelGGL((fwd_bf16_kernel<D, RB, NW>), grid, dim3(NW * 64), 0, s, p, hpb, n_hc);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+bool bf16_supported(int32_t d, int32_t Hq, int32_t Hkv) {
+    (void)Hq;
+    (void)Hkv;
+    return d == 32 || d == 64 || d == 128;
+}
+
+hipError_t launch_fwd_bf16(const Params& p, hipStream_t s) {
+    const int r = p.Hq / p.Hkv;
+    const bool wide = (r % 8) == 0;
+    switch (p.d) {
+        case 32: return wide ? launch<32, 2, 8>(p, s) : launch<32, 2, 4>(p, s);
+        case 64: return wide ? launch<64, 1, 8>(p, s) : launch<64, 2, 4>(p, s);
+        case 128: return wide ? launch<128, 1, 8>(p, s) : launch<128, 1, 4>(p, s);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace hta

@@ -1,0 +1,56 @@
+// gfx950 device helpers shared by the bf16 MFMA kernels: vector types, the 32x32x16 bf16 MFMA,
+// the LDS transpose read, cross-half exchanges.
+//
+// Lane layouts (wave of 64 lanes, lane = 32*hf + l32; checked on hardware):
+//   v_mfma_f32_32x32x16_bf16  D[32x32] += A[32x16] B[16x32]
+//     A operand: lane holds row m = l32, the 8 consecutive k values 8*hf .. 8*hf+7
+//     B operand: lane holds column n = l32, the 8 consecutive k values 8*hf .. 8*hf+7
+//     D (16 floats): lane holds column n = l32, register v holds row m = 8*(v/4) + 4*hf + (v%4)
+//   Because the contraction index of the accumulator's *registers* is m, an accumulator can be fed
+//   back (after conversion to bf16) as the B operand of a product that contracts over m: registers
+//   8*s .. 8*s+7 become k-step s, whose k-slot j of half hf is row m = 16*s + 8*(j/4) + 4*hf + (j%4).
+//   ds_read_b64_tr_b16: inside each group of 16 lanes, lane i receives element (i%4) of the four
+//     8-byte chunks addressed by lanes (i/4), (i/4)+4, (i/4)+8, (i/4)+12 of the group.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace hta {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+#define HTA_LDS __attribute__((address_space(3)))
+
+constexpr float LOG2E = 1.4426950408889634f;
+constexpr float LN2 = 0.6931471805599453f;
+
+__device__ inline floatx16 mfma32(bf16x8 a, bf16x8 b, floatx16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+__device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// value held by the lane 32 positions away (the other half of the wave)
+__device__ inline float other_half(float x) { return __shfl_xor(x, 32); }
+
+// Transposed 8-key fragment out of a row-major [row][col] bf16 tile in LDS.
+// The calling lane receives, for column `col0 + (lane%16)` of its 16-lane group, the elements of rows
+// row0 .. row0+3 (first read) and row0+8 .. row0+11 (second read).  `tile` points at element (0,0),
+// `stride` is the row pitch in elements; row0 / col0 must be uniform per 16-lane group, col0 % 4 == 0.
+__device__ inline bf16x8 lds_read_tr_8(const __bf16* tile, int stride, int row0, int col0, int lane) {
+    const int p = lane & 15;
+    const __bf16* a0 = tile + (row0 + (p >> 2)) * stride + col0 + 4 * (p & 3);
+    const __bf16* a1 = a0 + 8 * stride;
+    short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((HTA_LDS short4v*)(HTA_LDS char*)a0);
+    short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((HTA_LDS short4v*)(HTA_LDS char*)a1);
+    typedef short short8v __attribute__((ext_vector_type(8)));
+    short8v r = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, r);
+}
+
+}  // namespace hta

@@ -1,0 +1,106 @@
+"""Helpers of the GPU parity tests: move a seeded case to the device, run the library through the
+C-ABI binding, run the float64 oracle on the same bits, compare element by element."""
+from __future__ import annotations
+
+import sys
+
+import numpy as np
+import torch
+
+from oracle import hta_oracle as O
+from paper_2602_11235_amd import hta, inputs
+
+# |gpu - ref| <= ATOL + RTOL * |ref|, per element
+TOL = {"bf16": (2e-2, 2e-2), "fp32": (1e-4, 1e-4)}
+
+
+def say(msg: str) -> None:
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def to_torch(x: np.ndarray, dtype: str) -> torch.Tensor:
+    t = torch.from_numpy(np.ascontiguousarray(x)).to("cuda")
+    return t.to(torch.bfloat16) if dtype == "bf16" else t  # exact: values are bf16-representable
+
+
+def device_batch(case: inputs.Case) -> hta.Batch:
+    dt = case.cfg.dtype
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to("cuda")
+    max_hist = int(case.hist_len.max()) if case.batch else 0
+    max_tgt = int(case.n_targets.max()) if case.batch else 0
+    return hta.Batch(to_torch(case.q, dt), to_torch(case.k, dt), to_torch(case.v, dt), dev(case.q_offsets),
+                     dev(case.kv_offsets), dev(case.hist_len), dev(case.n_targets), max_hist, max_tgt, case.scale,
+                     case.cfg.layer)
+
+
+def host(t: torch.Tensor) -> np.ndarray:
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+def oracle_all(case: inputs.Case, with_bwd: bool):
+    layer = case.cfg.layer
+    out, lse = O.forward(case.q, case.k, case.v, case.q_offsets, case.kv_offsets, case.hist_len, case.n_targets,
+                         case.scale, layer)
+    if not with_bwd:
+        return out, lse
+    # the backward is fed the *oracle's* forward results: the GPU backward is checked against the exact
+    # gradient, not against a gradient contaminated by its own forward rounding
+    dq, dk, dv = O.backward(case.dout, case.q, case.k, case.v, out, lse, case.q_offsets, case.kv_offsets,
+                            case.hist_len, case.n_targets, case.scale, layer)
+    return out, lse, dq, dk, dv
+
+
+def assert_close(name: str, got: np.ndarray, ref: np.ndarray, dtype: str) -> None:
+    atol, rtol = TOL[dtype]
+    assert got.shape == ref.shape, f"{name}: shape {got.shape} vs {ref.shape}"
+    if got.size == 0:
+        return
+    assert np.isfinite(got).all(), f"{name}: non-finite values in GPU result"
+    err = np.abs(got - ref)
+    bound = atol + rtol * np.abs(ref)
+    worst = int(np.argmax(err - bound))
+    say(f"    {name}: max abs err {err.max():.3e}  max rel err {(err / (np.abs(ref) + 1e-30)).max():.3e}  "
+        f"ref absmax {np.abs(ref).max():.3e}")
+    assert (err <= bound).all(), (f"{name}: {int((err > bound).sum())} of {err.size} elements out of tolerance; worst at "
+                                  f"flat index {worst}: got {got.flat[worst]!r} ref {ref.flat[worst]!r}")
+
+
+def check_case(case: inputs.Case, with_bwd: bool, users=None) -> None:
+    """Run the library on the whole case; compare all users (users=None) or the listed ones against the
+    oracle run on exactly those users."""
+    dt = case.cfg.dtype
+    say(f"  case {case.cfg.name}: layer={case.cfg.layer} B={case.batch} total_q={case.total_q} total_kv={case.total_kv} "
+        f"Hq={case.cfg.Hq} Hkv={case.cfg.Hkv} d={case.cfg.head_dim} dtype={dt} bwd={with_bwd}")
+    batch = device_batch(case)
+    out, lse = batch.forward()
+    torch.cuda.synchronize()
+    g = {"out": host(out), "lse": host(lse)}
+    if with_bwd:
+        dq, dk, dv = batch.backward(to_torch(case.dout, dt))
+        torch.cuda.synchronize()
+        g.update(dq=host(dq), dk=host(dk), dv=host(dv))
+    if users is None:
+        ref_case, qrows, kvrows = case, slice(None), slice(None)
+    else:
+        ref_case = inputs.take_users(case, users)
+        qrows, kvrows = inputs.user_rows(case.q_offsets, users), inputs.user_rows(case.kv_offsets, users)
+    ref = oracle_all(ref_case, with_bwd)
+    assert_close("out", g["out"][qrows], ref[0], dt)
+    assert_close("lse", g["lse"][:, qrows], ref[1], dt)
+    if with_bwd:
+        assert_close("dq", g["dq"][qrows], ref[2], dt)
+        assert_close("dk", g["dk"][kvrows], ref[3], dt)
+        assert_close("dv", g["dv"][kvrows], ref[4], dt)
+
+
+def pick_users(case: inputs.Case, n_random: int, seed: int = 0):
+    """Extremes (shortest/longest history, fewest/most targets) plus a few seeded random users."""
+    picks = {int(np.argmin(case.hist_len)), int(np.argmax(case.hist_len)), int(np.argmin(case.n_targets)),
+             int(np.argmax(case.n_targets))}
+    u = inputs.uniform01(inputs.stream_key(seed, 99), 0, 4 * n_random)
+    for x in u:
+        if len(picks) >= 4 + n_random:
+            break
+        picks.add(int(x * case.batch) % case.batch)
+    return sorted(picks)
