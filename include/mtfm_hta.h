@@ -124,6 +124,23 @@ MTFM_HTA_API int mtfm_hta_validate_host(const int32_t* q_offsets, const int32_t*
                            const int32_t* n_targets, int32_t batch, int64_t total_q, int64_t total_kv,
                            int32_t max_hist, int32_t max_targets, int layer);
 
+/*
+ * Optional per-kernel timing (benchmarks, profiling).  mtfm_hta_timing_enable(slots) creates `slots`
+ * HIP event pairs per kernel kind (slots <= 0: destroy them and switch timing off, the default).  While
+ * on, every call records an event pair on its stream around each kernel it enqueues, into a ring of
+ * `slots` entries per kind.  mtfm_hta_timing_read() waits for the recorded events of one kind (this is
+ * the only blocking call of the library), writes up to `capacity` durations in milliseconds to the HOST
+ * array `ms`, oldest first, empties that ring and returns how many it wrote (or a negative status).
+ * Process-wide state; not meant to be toggled while another thread is inside a call.
+ */
+enum { MTFM_HTA_KERNEL_FWD = 0,      /* forward attention kernel */
+       MTFM_HTA_KERNEL_BWD_PRE = 1,  /* delta, self-key terms, dq accumulator initialisation */
+       MTFM_HTA_KERNEL_BWD_MAIN = 2, /* dK/dV/dQ over history key tiles */
+       MTFM_HTA_KERNEL_BWD_POST = 3, /* dq accumulator -> output dtype */
+       MTFM_HTA_N_KERNELS = 4 };
+MTFM_HTA_API int mtfm_hta_timing_enable(int slots);
+MTFM_HTA_API int mtfm_hta_timing_read(int kernel, float* ms, int capacity);
+
 /* Message for the calling thread's most recent non-OK status ("" if none).  Points to thread-local
  * static storage owned by the library: do not free; valid until the thread's next failing call. */
 MTFM_HTA_API const char* mtfm_hta_last_error(void);

@@ -11,7 +11,7 @@ LIB = os.path.join(HERE, "libmtfm_hta.so")
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fvisibility=hidden",
-    "-Wall", "-Wextra", "-Wno-unused-parameter",
+    "-Wall", "-Wextra", "-Wno-unused-parameter", "-munsafe-fp-atomics",
     # packed fp32 VALU forms are kept off for every device function in this library
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
 ]

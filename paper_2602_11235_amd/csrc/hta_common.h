@@ -47,6 +47,10 @@ hipError_t launch_bwd_fp32(const Params& p, hipStream_t s);
 hipError_t launch_fwd_bf16(const Params& p, hipStream_t s);
 hipError_t launch_bwd_bf16(const Params& p, hipStream_t s);
 bool bf16_supported(int32_t d, int32_t Hq, int32_t Hkv);
+// event hooks around each kernel (no-ops unless timing was enabled through the C ABI); `kind` is one of the
+// MTFM_HTA_KERNEL_* values
+void timing_begin(int kind, hipStream_t s);
+void timing_end(int kind, hipStream_t s);
 // fill `n` 32-bit words with zero (a kernel, so that a caller may capture the call in a HIP graph)
 hipError_t launch_zero_words(void* ptr, size_t n_words, hipStream_t s);
 

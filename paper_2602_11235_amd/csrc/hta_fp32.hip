@@ -5,6 +5,7 @@
 // Mask rules 1 and 3 (Section 3.2.2): the keys a query token `tok` may attend to are the L_b history
 // tokens, plus itself when it is a target token (tok >= L_b).  So the visible keys of a row are the
 // list [0, L_b) followed by at most one more entry, `tok` itself.
+#include "../../include/mtfm_hta.h"
 #include "hta_common.h"
 
 namespace hta {
@@ -197,14 +198,22 @@ hipError_t launch_zero_words(void* ptr, size_t n_words, hipStream_t s) {
     return hipGetLastError();
 }
 
-hipError_t launch_fwd_fp32(const Params& p, hipStream_t s) { return dispatch(p, s, false); }
+hipError_t launch_fwd_fp32(const Params& p, hipStream_t s) {
+    timing_begin(MTFM_HTA_KERNEL_FWD, s);
+    const hipError_t e = dispatch(p, s, false);
+    timing_end(MTFM_HTA_KERNEL_FWD, s);
+    return e;
+}
 
 hipError_t launch_bwd_fp32(const Params& p, hipStream_t s) {
     hipError_t e = launch_zero_words(p.dk, (size_t)p.total_kv * p.Hkv * p.d, s);
     if (e != hipSuccess) return e;
     e = launch_zero_words(p.dv, (size_t)p.total_kv * p.Hkv * p.d, s);
     if (e != hipSuccess) return e;
-    return dispatch(p, s, true);
+    timing_begin(MTFM_HTA_KERNEL_BWD_MAIN, s);
+    e = dispatch(p, s, true);
+    timing_end(MTFM_HTA_KERNEL_BWD_MAIN, s);
+    return e;
 }
 
 }  // namespace hta

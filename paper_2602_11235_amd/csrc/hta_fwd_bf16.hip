@@ -15,6 +15,7 @@
 // registers plus one exchange with the other half of the wave, and P^T in accumulator layout is
 // directly the B operand of O^T = V^T P^T.  V stays row-major in LDS and is read through the LDS
 // transpose read.
+#include "../../include/mtfm_hta.h"
 #include "hta_common.h"
 #include "hta_mfma.h"
 
@@ -268,12 +269,16 @@ bool bf16_supported(int32_t d, int32_t Hq, int32_t Hkv) {
 hipError_t launch_fwd_bf16(const Params& p, hipStream_t s) {
     const int r = p.Hq / p.Hkv;
     const bool wide = (r % 8) == 0;
+    hipError_t e;
+    timing_begin(MTFM_HTA_KERNEL_FWD, s);
     switch (p.d) {
-        case 32: return wide ? launch<32, 2, 8>(p, s) : launch<32, 2, 4>(p, s);
-        case 64: return wide ? launch<64, 1, 8>(p, s) : launch<64, 2, 4>(p, s);
-        case 128: return wide ? launch<128, 1, 8>(p, s) : launch<128, 1, 4>(p, s);
-        default: return hipErrorInvalidValue;
+        case 32: e = wide ? launch<32, 2, 8>(p, s) : launch<32, 2, 4>(p, s); break;
+        case 64: e = wide ? launch<64, 1, 8>(p, s) : launch<64, 2, 4>(p, s); break;
+        case 128: e = wide ? launch<128, 1, 8>(p, s) : launch<128, 1, 4>(p, s); break;
+        default: e = hipErrorInvalidValue;
     }
+    timing_end(MTFM_HTA_KERNEL_FWD, s);
+    return e;
 }
 
 }  // namespace hta

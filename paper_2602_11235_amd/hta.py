@@ -18,7 +18,8 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_LAUNCH = 0, -1, -2, -3,
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmtfm_hta.so")
 EXPORTS = ("mtfm_hta_workspace_bytes", "mtfm_hta_fwd", "mtfm_hta_bwd", "mtfm_hta_validate_host",
-           "mtfm_hta_last_error", "mtfm_hta_version")
+           "mtfm_hta_last_error", "mtfm_hta_version", "mtfm_hta_timing_enable", "mtfm_hta_timing_read")
+KERNEL_FWD, KERNEL_BWD_PRE, KERNEL_BWD_MAIN, KERNEL_BWD_POST = 0, 1, 2, 3
 
 _lib = None
 
@@ -53,6 +54,10 @@ def load_library() -> ctypes.CDLL:
     lib.mtfm_hta_last_error.argtypes = []
     lib.mtfm_hta_version.restype = ctypes.c_char_p
     lib.mtfm_hta_version.argtypes = []
+    lib.mtfm_hta_timing_enable.restype = ci
+    lib.mtfm_hta_timing_enable.argtypes = [ci]
+    lib.mtfm_hta_timing_read.restype = ci
+    lib.mtfm_hta_timing_read.argtypes = [ci, ctypes.POINTER(f32), ci]
     _lib = lib
     return lib
 
@@ -84,6 +89,19 @@ def mtfm_hta_version() -> str:
 
 def mtfm_hta_last_error() -> str:
     return load_library().mtfm_hta_last_error().decode()
+
+
+def mtfm_hta_timing_enable(slots: int) -> None:
+    _check(load_library().mtfm_hta_timing_enable(int(slots)))
+
+
+def mtfm_hta_timing_read(kernel: int, capacity: int = 4096):
+    """Durations (ms) recorded for one kernel kind since the last read, oldest first (blocks on the events)."""
+    buf = (ctypes.c_float * capacity)()
+    n = load_library().mtfm_hta_timing_read(int(kernel), buf, capacity)
+    if n < 0:
+        raise HtaError(n, "mtfm_hta_timing_read failed")
+    return [float(buf[i]) for i in range(n)]
 
 
 def mtfm_hta_workspace_bytes(layer, dtype, is_bwd, batch, total_q, total_kv, max_hist, max_targets, Hq, Hkv,

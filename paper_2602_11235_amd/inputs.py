@@ -243,3 +243,16 @@ def visible_pairs(hist_len: np.ndarray, n_targets: np.ndarray, Hq: int, layer: i
     if layer == LAYER_FULL:
         per = per + L * L
     return int(Hq * per.sum())
+
+
+def take_kv_group(case: Case, g: int) -> Case:
+    """The sub-problem of one key/value head and the r query heads that read it (heads of different kv
+    groups never interact, so a result on the slice is the result for those heads)."""
+    cfg = case.cfg
+    r = cfg.Hq // cfg.Hkv
+    sub = dataclasses.replace(cfg, name=f"{cfg.name}_g{g}", Hq=r, Hkv=1)
+    hs = slice(g * r, (g + 1) * r)
+    return Case(sub, case.hist_len, case.n_targets, case.kv_offsets, case.q_offsets,
+                np.ascontiguousarray(case.q[:, hs]), np.ascontiguousarray(case.k[:, g:g + 1]),
+                np.ascontiguousarray(case.v[:, g:g + 1]),
+                None if case.dout is None else np.ascontiguousarray(case.dout[:, hs]), case.scale)

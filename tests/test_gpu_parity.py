@@ -55,3 +55,20 @@ def test_bf16_large_logits_online_softmax():
     # logits spread over hundreds of units: exercises the running-max rescale across tiles
     c = custom("bf16_large_logits", FULL, [300, 70], [5, 40], 4, 1, 64, "bf16", std=3.0)
     check_case(c, with_bwd=False)
+
+
+# ------------------------------------------------------------------------------ bf16 backward
+@pytest.mark.parametrize("layer", [FULL, TARGET])
+@pytest.mark.parametrize("Hq,Hkv,d", [(8, 2, 64), (4, 4, 64), (3, 1, 64), (16, 2, 128), (4, 2, 32)])
+def test_bf16_edge_cases_backward(layer, Hq, Hkv, d):
+    c = custom(f"bf16_bwd_edges_{Hq}_{Hkv}_{d}", layer, EDGE_HIST, EDGE_TGTS, Hq, Hkv, d, "bf16")
+    check_case(c, with_bwd=True)
+
+
+def test_c2_bf16_backward_full_batch():
+    check_case(inputs.make_case(inputs.CONFIGS["C2"]), with_bwd=True)
+
+
+def test_c3_bf16_forward_backward_sampled_users():
+    c = inputs.make_case(inputs.CONFIGS["C3"])
+    check_case(c, with_bwd=True, users=pick_users(c, 2))
