@@ -28,11 +28,12 @@ template <int D>
 struct Tile {
     static constexpr int KS = D + 8;  // K row pitch (elements): 16-byte pad keeps 16-byte row reads conflict-free
     static constexpr int VS = D + 8;  // V row pitch
-    static constexpr int LDS_ELEMS = BN * KS + BN * VS;
+    static constexpr int BUF_ELEMS = BN * KS + BN * VS;   // one K tile + one V tile
+    static constexpr int LDS_ELEMS = 2 * BUF_ELEMS;       // double buffered
 };
 
 template <int D, int RB, int NW>
-__global__ __launch_bounds__(NW * 64) void fwd_bf16_kernel(Params p, int hpb, int n_hc) {
+__global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb, int n_hc) {
     constexpr int NT = NW * 64;
     constexpr int KS = Tile<D>::KS, VS = Tile<D>::VS;
     constexpr int CPR = D / 8;                     // 16-byte chunks per K/V row
@@ -40,8 +41,6 @@ __global__ __launch_bounds__(NW * 64) void fwd_bf16_kernel(Params p, int hpb, in
     constexpr int CH = (NCH + NT - 1) / NT;        // chunks per thread
     constexpr int NKS = D / 16, NDB = D / 32, NKB = BN / 32;
     __shared__ __attribute__((aligned(16))) __bf16 smem[Tile<D>::LDS_ELEMS];
-    __bf16* Ks = smem;
-    __bf16* Vs = smem + BN * KS;
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
     const int b = blockIdx.z;
@@ -101,93 +100,99 @@ __global__ __launch_bounds__(NW * 64) void fwd_bf16_kernel(Params p, int hpb, in
             }
         }
     };
-    auto store_tile = [&]() {
+    auto store_tile = [&](int buf) {
+        __bf16* Kd = smem + buf * Tile<D>::BUF_ELEMS;
+        __bf16* Vd = Kd + BN * KS;
 #pragma unroll
         for (int i = 0; i < CH; i++) {
             const int c = tid + i * NT;
             if (c < NCH) {
                 const int key = c / CPR, dc = c % CPR;
-                *(uint4*)(Ks + key * KS + dc * 8) = kreg[i];
-                *(uint4*)(Vs + key * VS + dc * 8) = vreg[i];
+                *(uint4*)(Kd + key * KS + dc * 8) = kreg[i];
+                *(uint4*)(Vd + key * VS + dc * 8) = vreg[i];
             }
         }
     };
 
-    if (n_kt > 0) load_tile(0);
-    for (int t = 0; t < n_kt; t++) {
-        __syncthreads();  // everyone is done reading the previous tile
-        store_tile();
-        __syncthreads();
-        if (t + 1 < n_kt) load_tile(t + 1);  // in flight while this tile is consumed
-
+    // One online-softmax step over a 32-key sub-tile.  `n_live` = number of keys of the sub-tile that are
+    // inside the history (32 except in the ragged last tile).
+    auto subtile = [&](const __bf16* Ks, const __bf16* Vs, int kb, int n_live) {
         // S^T[key][row] = sum_d K[key][d] Q[row][d]
-        floatx16 S[RB][NKB];
+        floatx16 S[RB];
 #pragma unroll
         for (int rb = 0; rb < RB; rb++)
 #pragma unroll
-            for (int kb = 0; kb < NKB; kb++)
+            for (int v = 0; v < 16; v++) S[rb][v] = 0.f;
 #pragma unroll
-                for (int v = 0; v < 16; v++) S[rb][kb][v] = 0.f;
+        for (int ks = 0; ks < NKS; ks++) {
+            const bf16x8 kf = *(const bf16x8*)(Ks + (kb * 32 + l32) * KS + ks * 16 + 8 * hf);
 #pragma unroll
-        for (int kb = 0; kb < NKB; kb++) {
+            for (int rb = 0; rb < RB; rb++) S[rb] = mfma32(kf, qf[rb][ks], S[rb]);
+        }
+        if (n_live < 32) {  // ragged: keys >= L_b are not visible
 #pragma unroll
-            for (int ks = 0; ks < NKS; ks++) {
-                const bf16x8 kf = *(const bf16x8*)(Ks + (kb * 32 + l32) * KS + ks * 16 + 8 * hf);
+            for (int v = 0; v < 16; v++) {
+                if (8 * (v / 4) + 4 * hf + (v % 4) >= n_live) {
 #pragma unroll
-                for (int rb = 0; rb < RB; rb++) S[rb][kb] = mfma32(kf, qf[rb][ks], S[rb][kb]);
+                    for (int rb = 0; rb < RB; rb++) S[rb][v] = -INFINITY;
+                }
             }
         }
-        if (t == n_kt - 1 && (L % BN) != 0) {  // ragged last history tile: keys >= L_b are not visible
-#pragma unroll
-            for (int kb = 0; kb < NKB; kb++)
-#pragma unroll
-                for (int v = 0; v < 16; v++) {
-                    const int key = t * BN + kb * 32 + 8 * (v / 4) + 4 * hf + (v % 4);
-                    if (key >= L) {
-#pragma unroll
-                        for (int rb = 0; rb < RB; rb++) S[rb][kb][v] = -INFINITY;
-                    }
-                }
-        }
         // online softmax, one query row per lane (two lanes, 32 apart, share a row)
-        bf16x8 pf[RB][NKB][2];
+        bf16x8 pf[RB][2];
 #pragma unroll
         for (int rb = 0; rb < RB; rb++) {
-            float mx = -INFINITY;
+            float mx = S[rb][0];
 #pragma unroll
-            for (int kb = 0; kb < NKB; kb++)
-#pragma unroll
-                for (int v = 0; v < 16; v++) mx = fmaxf(mx, S[rb][kb][v]);
+            for (int v = 1; v < 16; v++) mx = fmaxf(mx, S[rb][v]);
             mx = fmaxf(mx, other_half(mx));
             const float m_new = fmaxf(m[rb], mx * c2);
-            const float alpha = fast_exp2(m[rb] - m_new);
-            m[rb] = m_new;
+            if (__builtin_amdgcn_ballot_w64(m_new != m[rb]) != 0) {  // some row of the wave raised its maximum
+                const float alpha = fast_exp2(m[rb] - m_new);
+                m[rb] = m_new;
+                l[rb] *= alpha;
+#pragma unroll
+                for (int db = 0; db < NDB; db++)
+#pragma unroll
+                    for (int v = 0; v < 16; v++) O[rb][db][v] *= alpha;
+            }
             float psum = 0.f;
 #pragma unroll
-            for (int kb = 0; kb < NKB; kb++)
-#pragma unroll
-                for (int v = 0; v < 16; v++) {
-                    const float pv = fast_exp2(fmaf(S[rb][kb][v], c2, -m_new));
-                    psum += pv;
-                    pf[rb][kb][v / 8][v % 8] = (__bf16)pv;
-                }
-            l[rb] = fmaf(l[rb], alpha, psum);
-#pragma unroll
-            for (int db = 0; db < NDB; db++)
-#pragma unroll
-                for (int v = 0; v < 16; v++) O[rb][db][v] *= alpha;
+            for (int v = 0; v < 16; v++) {
+                const float pv = fast_exp2(fmaf(S[rb][v], c2, -m_new));
+                psum += pv;
+                pf[rb][v / 8][v % 8] = (__bf16)pv;
+            }
+            l[rb] += psum;
         }
         // O^T[d][row] += sum_key V[key][d] P^T[key][row]
 #pragma unroll
         for (int db = 0; db < NDB; db++)
 #pragma unroll
-            for (int kb = 0; kb < NKB; kb++)
+            for (int s2 = 0; s2 < 2; s2++) {
+                const bf16x8 vf = lds_read_tr_8(Vs, VS, kb * 32 + 16 * s2 + 4 * hf, db * 32 + 16 * ((lane >> 4) & 1), lane);
 #pragma unroll
-                for (int s2 = 0; s2 < 2; s2++) {
-                    const bf16x8 vf = lds_read_tr_8(Vs, VS, kb * 32 + 16 * s2 + 4 * hf, db * 32 + 16 * ((lane >> 4) & 1), lane);
-#pragma unroll
-                    for (int rb = 0; rb < RB; rb++) O[rb][db] = mfma32(vf, pf[rb][kb][s2], O[rb][db]);
-                }
+                for (int rb = 0; rb < RB; rb++) O[rb][db] = mfma32(vf, pf[rb][s2], O[rb][db]);
+            }
+    };
+
+    if (n_kt > 0) {
+        load_tile(0);
+        store_tile(0);
+        __syncthreads();
+    }
+    for (int t = 0; t < n_kt; t++) {
+        const __bf16* Ks = smem + (t & 1) * Tile<D>::BUF_ELEMS;
+        const __bf16* Vs = Ks + BN * KS;
+        if (t + 1 < n_kt) load_tile(t + 1);  // global loads in flight while this tile is consumed
+        const int live = L - t * BN;         // keys of this tile inside the history (>= 1)
+#pragma unroll 1
+        for (int kb = 0; kb < NKB; kb++) {
+            const int n_live = live - kb * 32;
+            if (n_live > 0) subtile(Ks, Vs, kb, n_live);
+        }
+        if (t + 1 < n_kt) store_tile((t + 1) & 1);  // the other buffer: last read before the previous barrier
+        __syncthreads();
     }
 
     // epilogue: self key of target rows (rule 3), normalisation, stores
