@@ -23,6 +23,7 @@ namespace hta {
 namespace {
 
 constexpr int BN = 64;  // keys per LDS tile
+constexpr float RESCALE_SLACK = 8.f;  // log2 units a row's logits may exceed its softmax reference before a rescale
 
 template <int D>
 struct Tile {
@@ -138,17 +139,22 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb,
                 }
             }
         }
-        // online softmax, one query row per lane (two lanes, 32 apart, share a row)
+        // Online softmax, one query row per lane (two lanes, 32 apart, share a row).  The reference m[rb]
+        // of a row only has to bound its logits from above up to a factor 2^RESCALE_SLACK: weights are
+        // exp2(s - m) <= 2^RESCALE_SLACK, sums and outputs share the reference, and the final division by l
+        // removes it.  So the accumulators are rescaled only when some row of the wave outgrows the slack,
+        // which after the first tiles almost never happens.
         bf16x8 pf[RB][2];
 #pragma unroll
         for (int rb = 0; rb < RB; rb++) {
             float mx = S[rb][0];
 #pragma unroll
             for (int v = 1; v < 16; v++) mx = fmaxf(mx, S[rb][v]);
-            mx = fmaxf(mx, other_half(mx));
-            const float m_new = fmaxf(m[rb], mx * c2);
-            if (__builtin_amdgcn_ballot_w64(m_new != m[rb]) != 0) {  // some row of the wave raised its maximum
-                const float alpha = fast_exp2(m[rb] - m_new);
+            mx = fmaxf(mx, other_half(mx)) * c2;
+            const bool grow = mx > m[rb] + RESCALE_SLACK;
+            if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+                const float m_new = grow ? mx : m[rb];
+                const float alpha = fast_exp2(m[rb] - m_new);  // 1 for the rows that keep their reference
                 m[rb] = m_new;
                 l[rb] *= alpha;
 #pragma unroll
@@ -156,14 +162,14 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb,
 #pragma unroll
                     for (int v = 0; v < 16; v++) O[rb][db][v] *= alpha;
             }
-            float psum = 0.f;
+            const float mref = m[rb];
 #pragma unroll
-            for (int v = 0; v < 16; v++) {
-                const float pv = fast_exp2(fmaf(S[rb][v], c2, -m_new));
-                psum += pv;
-                pf[rb][v / 8][v % 8] = (__bf16)pv;
-            }
-            l[rb] += psum;
+            for (int v = 0; v < 16; v++) pf[rb][v / 8][v % 8] = (__bf16)fast_exp2(fmaf(S[rb][v], c2, -mref));
+            // the row sum uses the same rounded weights as the P V product
+            float l0 = l[rb], l1 = 0.f;
+            add_bf16x8(l0, l1, pf[rb][0]);
+            add_bf16x8(l0, l1, pf[rb][1]);
+            l[rb] = l0 + l1;
         }
         // O^T[d][row] += sum_key V[key][d] P^T[key][row]
 #pragma unroll
@@ -181,6 +187,9 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb,
         store_tile(0);
         __syncthreads();
     }
+    // Q fragments must have landed before the loop: otherwise the in-order load counter forces every
+    // iteration to wait for its own freshly issued prefetch
+    wait_vmem_loads();
     for (int t = 0; t < n_kt; t++) {
         const __bf16* Ks = smem + (t & 1) * Tile<D>::BUF_ELEMS;
         const __bf16* Vs = Ks + BN * KS;

@@ -35,8 +35,30 @@ __device__ inline floatx16 mfma32(bf16x8 a, bf16x8 b, floatx16 c) {
 
 __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// value held by the lane 32 positions away (the other half of the wave)
-__device__ inline float other_half(float x) { return __shfl_xor(x, 32); }
+// value held by the lane 32 positions away (the other half of the wave); v_permlane32_swap is a VALU
+// exchange of the upper half of its first operand with the lower half of its second
+__device__ inline float other_half(float x) {
+    const unsigned u = __builtin_bit_cast(unsigned, x);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    // lanes 0..31 now hold (own, upper partner), lanes 32..63 hold (lower partner, own)
+    return __builtin_bit_cast(float, (threadIdx.x & 32) ? r[0] : r[1]);
+}
+
+// acc + x[0] + x[1] + ... + x[7] for eight packed bf16 values (v_dot2c_f32_bf16 against packed ones), two chains
+__device__ inline void add_bf16x8(float& acc0, float& acc1, bf16x8 x) {
+    bf16x2 one;
+    one[0] = (__bf16)1.0f;
+    one[1] = (__bf16)1.0f;
+    const bf16x2 a = __builtin_shufflevector(x, x, 0, 1), b = __builtin_shufflevector(x, x, 2, 3);
+    const bf16x2 c = __builtin_shufflevector(x, x, 4, 5), d = __builtin_shufflevector(x, x, 6, 7);
+    acc0 = __builtin_amdgcn_fdot2_f32_bf16(a, one, acc0, false);
+    acc1 = __builtin_amdgcn_fdot2_f32_bf16(b, one, acc1, false);
+    acc0 = __builtin_amdgcn_fdot2_f32_bf16(c, one, acc0, false);
+    acc1 = __builtin_amdgcn_fdot2_f32_bf16(d, one, acc1, false);
+}
+
+// wait until every outstanding vector-memory load of this wave has landed
+__device__ inline void wait_vmem_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 
 // Transposed 8-key fragment out of a row-major [row][col] bf16 tile in LDS.
 // The calling lane receives, for column `col0 + (lane%16)` of its 16-lane group, the elements of rows
