@@ -122,8 +122,8 @@ def main() -> int:
         step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    kinds = {"fwd": hta.KERNEL_FWD, "bwd_pre": hta.KERNEL_BWD_PRE, "bwd_main": hta.KERNEL_BWD_MAIN,
-             "bwd_post": hta.KERNEL_BWD_POST}
+    kinds = {"fwd": hta.KERNEL_FWD, "bwd_pre": hta.KERNEL_BWD_PRE, "bwd_dq": hta.KERNEL_BWD_DQ,
+             "bwd_dkdv": hta.KERNEL_BWD_DKDV}
     kernel_ms = {name: hta.mtfm_hta_timing_read(kind) for name, kind in kinds.items()}
     hta.mtfm_hta_timing_enable(0)
 
@@ -134,9 +134,10 @@ def main() -> int:
     flops_step = 14.0 * d * pairs
     value = flops_step / (ms_per_step * 1e-3) / 1e12
 
-    # algorithmic FLOPs per launch: the forward kernel does every visible pair (self keys included), the
-    # backward main kernel the history pairs (the self-key terms are done by bwd_pre)
-    flops = {"fwd": 4.0 * d * pairs, "bwd_main": 10.0 * d * hist_pairs}
+    # Algorithmic FLOPs per launch (what the method needs, not what the kernel executes): forward 4*d per
+    # visible pair; backward 10*d per pair, split between the two passes by the products they own -- dQ
+    # (S, dP, dQ = 6*d, of which S and dP are shared work credited once) and dK/dV (dV, dK = 4*d).
+    flops = {"fwd": 4.0 * d * pairs, "bwd_dq": 6.0 * d * pairs, "bwd_dkdv": 4.0 * d * hist_pairs}
     kernels = {}
     for name, ms in kernel_ms.items():
         if not ms:

@@ -104,8 +104,9 @@ MTFM_HTA_API int mtfm_hta_fwd(const void* q, const void* k, const void* v, void*
  *   dk, dv        out [total_kv][Hkv][head_dim] fully overwritten (in a target layer history rows receive the
  *                 gradient of every target query, target rows that of their own query)
  * `out` and `lse` must be what mtfm_hta_fwd produced for the same inputs.  Remaining arguments as in
- * mtfm_hta_fwd.  Sums across workgroups use float32 atomics, so results are reproducible to
- * rounding, not bitwise.
+ * mtfm_hta_fwd.  The bf16 path needs a workspace (mtfm_hta_workspace_bytes with is_bwd = 1) and is
+ * bitwise reproducible; the fp32 debug path sums dk/dv with float32 atomics, so it is reproducible to
+ * rounding only.
  */
 MTFM_HTA_API int mtfm_hta_bwd(const void* dout, const void* q, const void* k, const void* v, const void* out,
                  const float* lse, void* dq, void* dk, void* dv, const int32_t* q_offsets,
@@ -134,9 +135,9 @@ MTFM_HTA_API int mtfm_hta_validate_host(const int32_t* q_offsets, const int32_t*
  * Process-wide state; not meant to be toggled while another thread is inside a call.
  */
 enum { MTFM_HTA_KERNEL_FWD = 0,      /* forward attention kernel */
-       MTFM_HTA_KERNEL_BWD_PRE = 1,  /* delta, self-key terms, dq accumulator initialisation */
-       MTFM_HTA_KERNEL_BWD_MAIN = 2, /* dK/dV/dQ over history key tiles */
-       MTFM_HTA_KERNEL_BWD_POST = 3, /* dq accumulator -> output dtype */
+       MTFM_HTA_KERNEL_BWD_PRE = 1,  /* delta = <dout, out> per row, dk/dv of the target tokens' own keys */
+       MTFM_HTA_KERNEL_BWD_DQ = 2,   /* dq (row-stationary pass; the whole backward of the fp32 path) */
+       MTFM_HTA_KERNEL_BWD_DKDV = 3, /* dk, dv of the history keys (key-stationary pass) */
        MTFM_HTA_N_KERNELS = 4 };
 MTFM_HTA_API int mtfm_hta_timing_enable(int slots);
 MTFM_HTA_API int mtfm_hta_timing_read(int kernel, float* ms, int capacity);

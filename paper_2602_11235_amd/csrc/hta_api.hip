@@ -22,26 +22,18 @@ int fail(int code, const char* fmt, ...) {
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Workspace {
-    size_t delta_off, dq_off, dk_off, dv_off, total;
+    size_t delta_off, total;
 };
 
-// Layout of the caller's workspace.  Forward needs none.  Backward (bf16): delta [Hq][total_q] f32,
-// dq accumulator [total_q][Hq][d] f32, dk/dv accumulators [total_kv][Hkv][d] f32.
+// Layout of the caller's workspace.  Forward needs none.  Backward (bf16): delta [Hq][total_q] f32.
 // Backward (fp32): delta is computed inside the row kernel; nothing needed.
 Workspace plan_workspace(int dtype, int is_bwd, int64_t total_q, int64_t total_kv, int32_t Hq, int32_t Hkv,
                          int32_t d) {
-    Workspace w{0, 0, 0, 0, 0};
+    (void)total_kv; (void)Hkv; (void)d;
+    Workspace w{0, 0};
     if (!is_bwd || dtype == MTFM_HTA_FP32) return w;
-    size_t off = 0;
-    w.delta_off = off;
-    off += align256((size_t)total_q * Hq * sizeof(float));
-    w.dq_off = off;
-    off += align256((size_t)total_q * Hq * d * sizeof(float));
-    w.dk_off = off;
-    off += align256((size_t)total_kv * Hkv * d * sizeof(float));
-    w.dv_off = off;
-    off += align256((size_t)total_kv * Hkv * d * sizeof(float));
-    w.total = off;
+    w.delta_off = 0;
+    w.total = align256((size_t)total_q * Hq * sizeof(float));
     return w;
 }
 
@@ -172,9 +164,6 @@ int mtfm_hta_bwd(const void* dout, const void* q, const void* k, const void* v, 
     if (w.total > 0) {
         char* base = (char*)workspace;
         p.delta = (float*)(base + w.delta_off);
-        p.dq_acc = (float*)(base + w.dq_off);
-        p.dk_acc = (float*)(base + w.dk_off);
-        p.dv_acc = (float*)(base + w.dv_off);
     }
     hipStream_t s = (hipStream_t)stream;
     hipError_t e = dtype == MTFM_HTA_FP32 ? hta::launch_bwd_fp32(p, s) : hta::launch_bwd_bf16(p, s);

@@ -5,25 +5,26 @@
 //   P = exp(scale S - lse),  dP = dO V^T,  dS = P o (dP - delta),  delta_i = <dO_i, O_i>
 //   dV = P^T dO,  dK = scale dS^T Q  (both summed over the query heads of the kv group),  dQ = scale dS K
 //
-// Three kernels:
-//   1. bwd_pre:  delta for every (row, head); the self-key terms of target rows (rule 3: a target
-//      key is seen by its own row only, so its dk/dv come from that row alone and are written here,
-//      final, in bf16); and the float32 dq accumulator initialised to the self term (zero for
-//      history rows).
-//   2. bwd_main: one workgroup per (user, kv head, tile of BN history keys).  K/V tile in LDS,
-//      shared by all query heads of the group.  Each wave walks over (head, 32-row block) units:
-//      five 32x32x16 bf16 MFMA products per unit and 32-key sub-block, dK/dV kept in registers for
-//      the whole walk, dQ added to the float32 accumulator with atomics (it is a sum over key
-//      tiles, i.e. over workgroups).  Only history keys are ever visited: target x target and
-//      history-row x target-key tiles do not exist under the hybrid mask.
-//   3. bwd_post: dq accumulator -> bf16.
-//
-// MFMA operand choreography (see hta_mfma.h for the lane layouts): S = Q K^T and dP = dO V^T are
-// computed with the query rows on the accumulator *registers* and the keys on the lanes, so P and
-// dS are directly the k-operand of the products that contract over rows (dV, dK).  dQ contracts
-// over keys, which sit on lanes, so dS takes one wave-private round trip through LDS.  Every
-// transposed operand (Q^T, dO^T, K^T, dS^T) is produced by the LDS transpose read from a row-major
-// tile; nothing is transposed when staged.
+// Three kernels, no atomics, no float32 staging of any gradient:
+//   1. bwd_pre:  delta for every (row, head), and the self-key terms of target rows' keys (rule 3: a
+//      target key is seen by its own row only, so its dk/dv come from that row alone and are written
+//      here, final, in bf16).
+//   2. bwd_dq:   row-stationary, the forward kernel's decomposition: a wave keeps query rows (Q, dO, dQ) in
+//      registers and streams the history K/V tiles through LDS.  S^T = K Q^T and dP^T = V dO^T have
+//      the query row on the lane, so lse and delta are one register each and dS^T in accumulator layout
+//      is directly the k-operand of dQ^T = K^T dS^T.  The self key of a target row is one extra term
+//      in the epilogue.  dq is written once.
+//   3. bwd_dkdv: key-stationary: a wave owns 32 history keys (K, V fragments and the dK, dV accumulators
+//      stay in registers for the whole kernel), the workgroup streams (head, 32-row block) tiles of Q
+//      and dO through LDS, shared by its waves.  S = Q K^T and dP = dO V^T have the key on the lane, so
+//      P and dS in accumulator layout are directly the k-operand of dV = P^T dO and dK = dS^T Q.
+//      dk/dv of history keys are written once.
+// S and dP are thus computed twice (7 matrix products instead of 5); in exchange neither dQ nor
+// dK/dV ever crosses a workgroup, which removes a float32 accumulator three times the size of q, its
+// zero-fill and conversion passes, and an atomic traffic of several GB per call.
+// Only history keys are ever visited: target x target and history-row x target-key tiles do not exist
+// under the hybrid mask.  Every transposed operand (K^T, Q^T, dO^T) is produced by the LDS transpose
+// read from a row-major tile; nothing is transposed when staged.
 #include "../../include/mtfm_hta.h"
 #include "hta_common.h"
 #include "hta_mfma.h"
@@ -83,9 +84,6 @@ __global__ __launch_bounds__(256) void bwd_pre_kernel(Params p) {
         }
         const float delta = group_sum(part, LPR);
         if (sub == 0) p.delta[(int64_t)h * p.total_q + q_row] = delta;
-        float dq0[8];
-#pragma unroll
-        for (int j = 0; j < 8; j++) dq0[j] = 0.f;
         if (is_target) {
             const bf16x8 qv = *(const bf16x8*)(qg + off);
             float qf[8], sp = 0.f, dpp = 0.f;
@@ -101,14 +99,10 @@ __global__ __launch_bounds__(256) void bwd_pre_kernel(Params p) {
             const float ds = pw * (dp - delta) * p.scale;
 #pragma unroll
             for (int j = 0; j < 8; j++) {
-                dq0[j] = ds * kself[j];
                 dk_t[j] = fmaf(ds, qf[j], dk_t[j]);
                 dv_t[j] = fmaf(pw, dof[j], dv_t[j]);
             }
         }
-        float* dqa = p.dq_acc + off;
-        *(float4*)dqa = make_float4(dq0[0], dq0[1], dq0[2], dq0[3]);
-        *(float4*)(dqa + 4) = make_float4(dq0[4], dq0[5], dq0[6], dq0[7]);
     }
     if (is_target) {
         bf16x8 dk8, dv8;
@@ -122,240 +116,389 @@ __global__ __launch_bounds__(256) void bwd_pre_kernel(Params p) {
     }
 }
 
-// ---------------------------------------------------------------------------------------- post
-__global__ __launch_bounds__(256) void bwd_post_kernel(const float* __restrict__ acc, __bf16* __restrict__ dq, int64_t n8) {
-    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (; i < n8; i += stride) {
-        const float4 a = *(const float4*)(acc + i * 8);
-        const float4 c = *(const float4*)(acc + i * 8 + 4);
-        bf16x8 o;
-        o[0] = (__bf16)a.x; o[1] = (__bf16)a.y; o[2] = (__bf16)a.z; o[3] = (__bf16)a.w;
-        o[4] = (__bf16)c.x; o[5] = (__bf16)c.y; o[6] = (__bf16)c.z; o[7] = (__bf16)c.w;
-        *(bf16x8*)(dq + i * 8) = o;
+// ---------------------------------------------------------------------------------------- dQ
+constexpr int BN = 64;  // keys per LDS tile of the dQ kernel
+
+template <int D, int RB, int NW>
+__global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(Params p, int hpb, int n_hc) {
+    constexpr int NT = NW * 64;
+    constexpr int KS = D + 8;                      // K/V row pitch (elements)
+    constexpr int BUF_ELEMS = 2 * BN * KS;         // one K tile + one V tile
+    constexpr int CPR = D / 8, NCH = BN * CPR, CH = (NCH + NT - 1) / NT;
+    constexpr int NKS = D / 16, NDB = D / 32, NKB = BN / 32;
+    __shared__ __attribute__((aligned(16))) __bf16 smem[2 * BUF_ELEMS];
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
+    const int b = blockIdx.z;
+    const int g = blockIdx.y / n_hc, hc = blockIdx.y % n_hc;
+    const int L = p.hist_len[b], T = p.n_targets[b];
+    const int n_rows = p.layer == 0 ? L + T : T;
+    const int BM = (NW / hpb) * RB * 32;
+    const int tile_row0 = blockIdx.x * BM;
+    if (tile_row0 >= n_rows) return;  // uniform for the whole workgroup
+    const int r = p.Hq / p.Hkv;
+    const int h = g * r + hc * hpb + wave % hpb;
+    const int wrow0 = tile_row0 + (wave / hpb) * (RB * 32);
+    const int tok_shift = p.layer == 0 ? 0 : L;
+    const int64_t q_base = p.q_off[b], kv_base = p.kv_off[b];
+    const __bf16* kg = (const __bf16*)p.k;
+    const __bf16* vg = (const __bf16*)p.v;
+    const float c2 = p.scale * LOG2E;
+    const int dhalf16 = 16 * ((lane >> 4) & 1);
+
+    // per lane: one query row per row block (clamped past the end; never stored then)
+    bf16x8 qf[RB][NKS], dof[RB][NKS];
+    float lse2[RB], dl[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; rb++) {
+        int row = wrow0 + rb * 32 + l32;
+        row = row < n_rows ? row : n_rows - 1;
+        const int64_t off = ((q_base + row) * p.Hq + h) * D + 8 * hf;
+#pragma unroll
+        for (int ks = 0; ks < NKS; ks++) {
+            qf[rb][ks] = *(const bf16x8*)((const __bf16*)p.q + off + ks * 16);
+            dof[rb][ks] = *(const bf16x8*)((const __bf16*)p.dout + off + ks * 16);
+        }
+        lse2[rb] = p.lse[(int64_t)h * p.total_q + q_base + row] * LOG2E;
+        dl[rb] = p.delta[(int64_t)h * p.total_q + q_base + row];
+    }
+    floatx16 dQ[RB][NDB];  // dQ^T: [d (registers)][row (lanes)]
+#pragma unroll
+    for (int rb = 0; rb < RB; rb++)
+#pragma unroll
+        for (int db = 0; db < NDB; db++)
+#pragma unroll
+            for (int v = 0; v < 16; v++) dQ[rb][db][v] = 0.f;
+
+    const int n_kt = (L + BN - 1) / BN;
+    uint4 kreg[CH], vreg[CH];
+    auto load_tile = [&](int t) {
+#pragma unroll
+        for (int i = 0; i < CH; i++) {
+            const int c = tid + i * NT;
+            const int key = t * BN + c / CPR, dc = c % CPR;
+            kreg[i] = make_uint4(0, 0, 0, 0);
+            vreg[i] = make_uint4(0, 0, 0, 0);
+            if (c < NCH && key < L) {  // keys past the history are zero-filled
+                const int64_t off = ((kv_base + key) * p.Hkv + g) * D + dc * 8;
+                kreg[i] = *(const uint4*)(kg + off);
+                vreg[i] = *(const uint4*)(vg + off);
+            }
+        }
+    };
+    auto store_tile = [&](int buf) {
+        __bf16* Kd = smem + buf * BUF_ELEMS;
+        __bf16* Vd = Kd + BN * KS;
+#pragma unroll
+        for (int i = 0; i < CH; i++) {
+            const int c = tid + i * NT;
+            if (c < NCH) {
+                *(uint4*)(Kd + (c / CPR) * KS + (c % CPR) * 8) = kreg[i];
+                *(uint4*)(Vd + (c / CPR) * KS + (c % CPR) * 8) = vreg[i];
+            }
+        }
+    };
+    auto subtile = [&](const __bf16* Ks, const __bf16* Vs, int kb, int n_live) {
+        floatx16 S[RB], dP[RB];  // S^T, dP^T: [key (registers)][row (lanes)]
+#pragma unroll
+        for (int ks = 0; ks < NKS; ks++) {
+            const bf16x8 kf = *(const bf16x8*)(Ks + (kb * 32 + l32) * KS + ks * 16 + 8 * hf);
+            const bf16x8 vf = *(const bf16x8*)(Vs + (kb * 32 + l32) * KS + ks * 16 + 8 * hf);
+#pragma unroll
+            for (int rb = 0; rb < RB; rb++) {
+                if (ks == 0) {
+                    const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                    S[rb] = mfma32(kf, qf[rb][ks], zero);
+                    dP[rb] = mfma32(vf, dof[rb][ks], zero);
+                } else {
+                    S[rb] = mfma32(kf, qf[rb][ks], S[rb]);
+                    dP[rb] = mfma32(vf, dof[rb][ks], dP[rb]);
+                }
+            }
+        }
+        if (n_live < 32) {  // ragged: keys >= L_b are not visible (P = 0)
+#pragma unroll
+            for (int v = 0; v < 16; v++) {
+                if (8 * (v / 4) + 4 * hf + (v % 4) >= n_live) {
+#pragma unroll
+                    for (int rb = 0; rb < RB; rb++) S[rb][v] = -INFINITY;
+                }
+            }
+        }
+        bf16x8 dsb[RB][2];
+#pragma unroll
+        for (int rb = 0; rb < RB; rb++)
+#pragma unroll
+            for (int v = 0; v < 16; v++) {
+                const float pw = fast_exp2(fmaf(S[rb][v], c2, -lse2[rb]));
+                dsb[rb][v / 8][v % 8] = (__bf16)(pw * (dP[rb][v] - dl[rb]));
+            }
+        // dQ^T[d][row] += sum_key K[key][d] dS^T[key][row]
+#pragma unroll
+        for (int db = 0; db < NDB; db++)
+#pragma unroll
+            for (int s2 = 0; s2 < 2; s2++) {
+                const bf16x8 ktf = lds_read_tr_8(Ks, KS, kb * 32 + 16 * s2 + 4 * hf, db * 32 + dhalf16, lane);
+#pragma unroll
+                for (int rb = 0; rb < RB; rb++) dQ[rb][db] = mfma32(ktf, dsb[rb][s2], dQ[rb][db]);
+            }
+    };
+
+    if (n_kt > 0) {
+        load_tile(0);
+        store_tile(0);
+        __syncthreads();
+    }
+    wait_vmem_loads();  // Q, dO, lse, delta have landed: the loop's load counter only tracks its own prefetch
+    for (int t = 0; t < n_kt; t++) {
+        const __bf16* Ks = smem + (t & 1) * BUF_ELEMS;
+        const __bf16* Vs = Ks + BN * KS;
+        if (t + 1 < n_kt) load_tile(t + 1);
+        const int live = L - t * BN;
+#pragma unroll 1
+        for (int kb = 0; kb < NKB; kb++) {
+            const int n_live = live - kb * 32;
+            if (n_live > 0) subtile(Ks, Vs, kb, n_live);
+        }
+        if (t + 1 < n_kt) store_tile((t + 1) & 1);
+        __syncthreads();
+    }
+
+    // epilogue: self key of target rows (rule 3), scale, store
+    __bf16* dqg = (__bf16*)p.dq;
+#pragma unroll
+    for (int rb = 0; rb < RB; rb++) {
+        const int row = wrow0 + rb * 32 + l32;
+        const bool live = row < n_rows;
+        const int tok = tok_shift + row;
+        if (live && tok >= L) {
+            const int64_t off = ((kv_base + tok) * p.Hkv + g) * D;
+            float sp = 0.f, dpp = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < NKS; ks++) {
+                const bf16x8 kk = *(const bf16x8*)(kg + off + ks * 16 + 8 * hf);
+                const bf16x8 vv = *(const bf16x8*)(vg + off + ks * 16 + 8 * hf);
+#pragma unroll
+                for (int j = 0; j < 8; j++) {
+                    sp = fmaf((float)qf[rb][ks][j], (float)kk[j], sp);
+                    dpp = fmaf((float)dof[rb][ks][j], (float)vv[j], dpp);
+                }
+            }
+            sp += other_half(sp);
+            dpp += other_half(dpp);
+            const float pw = fast_exp2(fmaf(sp, c2, -lse2[rb]));
+            const float ds = pw * (dpp - dl[rb]);
+#pragma unroll
+            for (int db = 0; db < NDB; db++)
+#pragma unroll
+                for (int v4 = 0; v4 < 4; v4++) {
+                    const bf16x4 kk = *(const bf16x4*)(kg + off + db * 32 + 8 * v4 + 4 * hf);
+#pragma unroll
+                    for (int j = 0; j < 4; j++) dQ[rb][db][4 * v4 + j] = fmaf(ds, (float)kk[j], dQ[rb][db][4 * v4 + j]);
+                }
+        }
+        if (live) {
+            __bf16* op = dqg + ((q_base + row) * p.Hq + h) * D;
+#pragma unroll
+            for (int db = 0; db < NDB; db++)
+#pragma unroll
+                for (int v4 = 0; v4 < 4; v4++) {
+                    bf16x4 o4;
+#pragma unroll
+                    for (int j = 0; j < 4; j++) o4[j] = (__bf16)(dQ[rb][db][4 * v4 + j] * p.scale);
+                    *(bf16x4*)(op + db * 32 + 8 * v4 + 4 * hf) = o4;
+                }
+        }
     }
 }
 
-// ---------------------------------------------------------------------------------------- main
-template <int D, int BN, int NW>
-struct BwdSmem {
-    static constexpr int KS = D + 8;       // K/V row pitch (elements)
-    static constexpr int QS = D + 8;       // wave-private Q/dO row pitch
-    static constexpr int SS = 32 + 8;      // wave-private dS [key][row] pitch
-    static constexpr int KV_ELEMS = 2 * BN * KS;
-    static constexpr int WAVE_ELEMS = 2 * 32 * QS + 32 * SS;
-    static constexpr size_t WAVE_BYTES = (size_t)WAVE_ELEMS * 2;
-    static constexpr size_t RED_BYTES = (size_t)BN * D * 4;   // float32 [key][d] reduction buffer, aliased on the wave regions
-    static constexpr size_t BYTES = (size_t)KV_ELEMS * 2 + (NW * WAVE_BYTES > RED_BYTES ? NW * WAVE_BYTES : RED_BYTES);
+// ---------------------------------------------------------------------------------------- dK, dV
+template <int D, int NW>
+struct DkdvSmem {
+    static constexpr int QS = D + 8;                    // Q/dO tile row pitch (elements)
+    static constexpr int TILE = 32 * QS;                // one 32-row tile
+    static constexpr size_t BUF_BYTES = (size_t)2 * TILE * 2 + 2 * 32 * sizeof(float);  // Q, dO, lse2[32], delta[32]
+    static constexpr size_t BYTES = 2 * BUF_BYTES;      // double buffered
 };
 
-template <int D, int BN, int NW>
-__global__ __launch_bounds__(NW * 64) void bwd_main_kernel(Params p) {
-    using SM = BwdSmem<D, BN, NW>;
-    constexpr int NT = NW * 64;
-    constexpr int KS = SM::KS, QS = SM::QS, SS = SM::SS;
-    constexpr int CPR = D / 8, NCH = BN * CPR;
-    constexpr int NKS = D / 16, NDB = D / 32, NKB = BN / 32;
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    __bf16* Ks = (__bf16*)smem_raw;
-    __bf16* Vs = Ks + BN * KS;
-    unsigned char* wave_base = smem_raw + (size_t)SM::KV_ELEMS * 2;
+// grid: x = tile of NW*32 history keys, y = kv head, z = user
+template <int D, int NW>
+__global__ __launch_bounds__(NW * 64, 2) void bwd_dkdv_kernel(Params p) {
+    using SM = DkdvSmem<D, NW>;
+    constexpr int NT = NW * 64, QS = SM::QS;
+    constexpr int CPR = D / 8, NCH = 32 * CPR, CH = (NCH + NT - 1) / NT;
+    constexpr int NKS = D / 16, NDB = D / 32;
+    __shared__ __attribute__((aligned(16))) unsigned char smem_raw[SM::BYTES];
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
-    const int b = blockIdx.z, g = blockIdx.y, kt = blockIdx.x;
+    const int b = blockIdx.z, g = blockIdx.y;
     const int L = p.hist_len[b], T = p.n_targets[b];
-    if (kt * BN >= L) return;  // uniform: this key tile does not exist for the user
+    const int key0 = blockIdx.x * (NW * 32);
+    if (key0 >= L) return;  // uniform: this key tile does not exist for the user
     const int n_rows = p.layer == 0 ? L + T : T;
     const int r = p.Hq / p.Hkv;
     const int64_t q_base = p.q_off[b], kv_base = p.kv_off[b];
-    const __bf16* qg = (const __bf16*)p.q;
-    const __bf16* dog = (const __bf16*)p.dout;
     const float c2 = p.scale * LOG2E;
-    const int key0 = kt * BN;
+    const int dhalf16 = 16 * ((lane >> 4) & 1);
+    const int kw = key0 + wave * 32;        // first key of this wave
+    const bool wave_live = kw < L;          // a wave past the history only helps staging
+    const bool key_live = kw + l32 < L;
 
-    // stage the K/V tile (keys past the history are zero-filled; their P and dS are forced to 0)
-    for (int c = tid; c < NCH; c += NT) {
-        const int key = c / CPR, dc = c % CPR;
-        uint4 kk = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
-        if (key0 + key < L) {
-            const int64_t off = ((kv_base + key0 + key) * p.Hkv + g) * D + dc * 8;
-            kk = *(const uint4*)((const __bf16*)p.k + off);
-            vv = *(const uint4*)((const __bf16*)p.v + off);
+    // stationary operands: K and V rows of the wave's keys (B operand of S = Q K^T and dP = dO V^T)
+    bf16x8 kf[NKS], vf[NKS];
+    {
+        const int key = key_live ? kw + l32 : L - 1;
+        const int64_t off = ((kv_base + key) * p.Hkv + g) * D + 8 * hf;
+#pragma unroll
+        for (int ks = 0; ks < NKS; ks++) {
+            kf[ks] = *(const bf16x8*)((const __bf16*)p.k + off + ks * 16);
+            vf[ks] = *(const bf16x8*)((const __bf16*)p.v + off + ks * 16);
         }
-        *(uint4*)(Ks + key * KS + dc * 8) = kk;
-        *(uint4*)(Vs + key * KS + dc * 8) = vv;
     }
-    __syncthreads();
-
-    __bf16* Qs = (__bf16*)(wave_base + wave * SM::WAVE_BYTES);
-    __bf16* dOs = Qs + 32 * QS;
-    __bf16* dSs = dOs + 32 * QS;
-
-    floatx16 dK[NKB][NDB], dV[NKB][NDB];  // [key m (registers)][d n (lanes)]
+    floatx16 dK[NDB], dV[NDB];  // [key (registers)][d (lanes)]
 #pragma unroll
-    for (int kb = 0; kb < NKB; kb++)
-#pragma unroll
-        for (int db = 0; db < NDB; db++)
-#pragma unroll
-            for (int v = 0; v < 16; v++) {
-                dK[kb][db][v] = 0.f;
-                dV[kb][db][v] = 0.f;
-            }
-    const bool ragged_keys = key0 + BN > L;
-    const int n_rb = (n_rows + 31) / 32;
-    const int n_units = n_rb * r;
-    const int dhalf = (lane >> 4) & 1;
-
-    for (int u = wave; u < n_units; u += NW) {
-        const int rb = u / r, h = g * r + u % r;
-        const int row0 = rb * 32;
-        // Q and dO rows of the unit: natural fragments (lane = row, 8 consecutive d per k-step) straight from
-        // global memory, and a copy in the wave's LDS region for the transposed reads
-        bf16x8 qf[NKS], dof[NKS];
-        {
-            int row = row0 + l32;
-            row = row < n_rows ? row : n_rows - 1;
-            const int64_t off = ((q_base + row) * p.Hq + h) * D + 8 * hf;
-#pragma unroll
-            for (int ks = 0; ks < NKS; ks++) {
-                qf[ks] = *(const bf16x8*)(qg + off + ks * 16);
-                dof[ks] = *(const bf16x8*)(dog + off + ks * 16);
-            }
-#pragma unroll
-            for (int ks = 0; ks < NKS; ks++) {
-                *(bf16x8*)(Qs + l32 * QS + ks * 16 + 8 * hf) = qf[ks];
-                *(bf16x8*)(dOs + l32 * QS + ks * 16 + 8 * hf) = dof[ks];
-            }
-        }
-        // per accumulator register: lse (log2 domain) and delta of its row; rows past the end get lse = +inf => P = 0
-        float lse2[16], dl[16];
+    for (int db = 0; db < NDB; db++)
 #pragma unroll
         for (int v = 0; v < 16; v++) {
-            const int row = row0 + 8 * (v / 4) + 4 * hf + (v % 4);
+            dK[db][v] = 0.f;
+            dV[db][v] = 0.f;
+        }
+
+    const int n_rb = (n_rows + 31) / 32;
+    const int n_units = n_rb * r;  // unit u = (32-row block u / r, head g*r + u % r)
+    uint4 qreg[CH], doreg[CH];
+    float sreg = 0.f;  // lane < 32 of wave 0: lse2 of row `lane`; lanes 32..63 of wave 0: delta of row lane-32
+    auto load_unit = [&](int u) {
+        const int row0 = (u / r) * 32, h = g * r + u % r;
+#pragma unroll
+        for (int i = 0; i < CH; i++) {
+            const int c = tid + i * NT;
+            if (c < NCH) {
+                int row = row0 + c / CPR;
+                row = row < n_rows ? row : n_rows - 1;
+                const int64_t off = ((q_base + row) * p.Hq + h) * D + (c % CPR) * 8;
+                qreg[i] = *(const uint4*)((const __bf16*)p.q + off);
+                doreg[i] = *(const uint4*)((const __bf16*)p.dout + off);
+            }
+        }
+        if (tid < 64) {
+            const int row = row0 + (tid & 31);
             const bool live = row < n_rows;
             const int64_t idx = (int64_t)h * p.total_q + q_base + (live ? row : n_rows - 1);
-            lse2[v] = live ? p.lse[idx] * LOG2E : INFINITY;
-            dl[v] = p.delta[idx];
+            // rows past the end get lse = +inf, i.e. P = 0
+            sreg = tid < 32 ? (live ? p.lse[idx] * LOG2E : INFINITY) : p.delta[idx];
         }
-        floatx16 dQ[NDB];  // [row m (registers)][d n (lanes)]
+    };
+    auto store_unit = [&](int buf) {
+        __bf16* Qd = (__bf16*)(smem_raw + buf * SM::BUF_BYTES);
+        __bf16* dOd = Qd + SM::TILE;
+        float* sd = (float*)(dOd + SM::TILE);
 #pragma unroll
-        for (int db = 0; db < NDB; db++)
-#pragma unroll
-            for (int v = 0; v < 16; v++) dQ[db][v] = 0.f;
-
-#pragma unroll
-        for (int kb = 0; kb < NKB; kb++) {
-            floatx16 S, dP;
-#pragma unroll
-            for (int v = 0; v < 16; v++) {
-                S[v] = 0.f;
-                dP[v] = 0.f;
+        for (int i = 0; i < CH; i++) {
+            const int c = tid + i * NT;
+            if (c < NCH) {
+                *(uint4*)(Qd + (c / CPR) * QS + (c % CPR) * 8) = qreg[i];
+                *(uint4*)(dOd + (c / CPR) * QS + (c % CPR) * 8) = doreg[i];
             }
+        }
+        if (tid < 64) sd[tid] = sreg;
+    };
+
+    if (n_units > 0) {
+        load_unit(0);
+        store_unit(0);
+    }
+    __syncthreads();
+    wait_vmem_loads();
+    for (int u = 0; u < n_units; u++) {
+        const __bf16* Qs = (const __bf16*)(smem_raw + (u & 1) * SM::BUF_BYTES);
+        const __bf16* dOs = Qs + SM::TILE;
+        const float* ss = (const float*)(dOs + SM::TILE);
+        if (u + 1 < n_units) load_unit(u + 1);
+        if (wave_live) {
+            floatx16 S, dP;  // [row (registers)][key (lanes)]
 #pragma unroll
             for (int ks = 0; ks < NKS; ks++) {
-                const bf16x8 kf = *(const bf16x8*)(Ks + (kb * 32 + l32) * KS + ks * 16 + 8 * hf);
-                const bf16x8 vf = *(const bf16x8*)(Vs + (kb * 32 + l32) * KS + ks * 16 + 8 * hf);
-                S = mfma32(qf[ks], kf, S);      // S[row][key]
-                dP = mfma32(dof[ks], vf, dP);   // dP[row][key]
+                const bf16x8 qa = *(const bf16x8*)(Qs + l32 * QS + ks * 16 + 8 * hf);
+                const bf16x8 da = *(const bf16x8*)(dOs + l32 * QS + ks * 16 + 8 * hf);
+                if (ks == 0) {
+                    const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                    S = mfma32(qa, kf[ks], zero);
+                    dP = mfma32(da, vf[ks], zero);
+                } else {
+                    S = mfma32(qa, kf[ks], S);
+                    dP = mfma32(da, vf[ks], dP);
+                }
             }
-            const bool key_dead = ragged_keys && (key0 + kb * 32 + l32 >= L);
             bf16x8 pb[2], dsb[2];
 #pragma unroll
-            for (int v = 0; v < 16; v++) {
-                float pw = fast_exp2(fmaf(S[v], c2, -lse2[v]));
-                pw = key_dead ? 0.f : pw;
-                const float ds = pw * (dP[v] - dl[v]);
-                pb[v / 8][v % 8] = (__bf16)pw;
-                dsb[v / 8][v % 8] = (__bf16)ds;
-            }
-            // dS^T to the wave's LDS region as [key][row]: this lane owns key l32 and rows 8j+4hf..+3
+            for (int j = 0; j < 4; j++) {  // registers 4j..4j+3 hold rows 8j+4hf .. 8j+4hf+3
+                const floatx4 l4 = *(const floatx4*)(ss + 8 * j + 4 * hf);
+                const floatx4 d4 = *(const floatx4*)(ss + 32 + 8 * j + 4 * hf);
 #pragma unroll
-            for (int j = 0; j < 4; j++) {
-                bf16x4 w;
-                w[0] = dsb[j / 2][4 * (j % 2) + 0];
-                w[1] = dsb[j / 2][4 * (j % 2) + 1];
-                w[2] = dsb[j / 2][4 * (j % 2) + 2];
-                w[3] = dsb[j / 2][4 * (j % 2) + 3];
-                *(bf16x4*)(dSs + l32 * SS + 8 * j + 4 * hf) = w;
+                for (int e = 0; e < 4; e++) {
+                    const int v = 4 * j + e;
+                    float pw = fast_exp2(fmaf(S[v], c2, -l4[e]));
+                    pw = key_live ? pw : 0.f;
+                    pb[v / 8][v % 8] = (__bf16)pw;
+                    dsb[v / 8][v % 8] = (__bf16)(pw * (dP[v] - d4[e]));
+                }
             }
             // dV[key][d] += P^T[key][row] dO[row][d];  dK[key][d] += dS^T[key][row] Q[row][d]
 #pragma unroll
             for (int db = 0; db < NDB; db++)
 #pragma unroll
                 for (int s2 = 0; s2 < 2; s2++) {
-                    const bf16x8 dot = lds_read_tr_8(dOs, QS, 16 * s2 + 4 * hf, db * 32 + 16 * dhalf, lane);
-                    const bf16x8 qt = lds_read_tr_8(Qs, QS, 16 * s2 + 4 * hf, db * 32 + 16 * dhalf, lane);
-                    dV[kb][db] = mfma32(pb[s2], dot, dV[kb][db]);
-                    dK[kb][db] = mfma32(dsb[s2], qt, dK[kb][db]);
+                    const bf16x8 dot = lds_read_tr_8(dOs, QS, 16 * s2 + 4 * hf, db * 32 + dhalf16, lane);
+                    const bf16x8 qt = lds_read_tr_8(Qs, QS, 16 * s2 + 4 * hf, db * 32 + dhalf16, lane);
+                    dV[db] = mfma32(pb[s2], dot, dV[db]);
+                    dK[db] = mfma32(dsb[s2], qt, dK[db]);
                 }
-            // dQ[row][d] += dS[row][key] K[key][d]
-#pragma unroll
-            for (int s2 = 0; s2 < 2; s2++) {
-                const bf16x8 dst = lds_read_tr_8(dSs, SS, 16 * s2 + 4 * hf, 16 * dhalf, lane);
-#pragma unroll
-                for (int db = 0; db < NDB; db++) {
-                    const bf16x8 ktf = lds_read_tr_8(Ks + kb * 32 * KS, KS, 16 * s2 + 4 * hf, db * 32 + 16 * dhalf, lane);
-                    dQ[db] = mfma32(dst, ktf, dQ[db]);
-                }
-            }
         }
-        // dQ partial of this key tile -> float32 accumulator (lanes cover 32 consecutive d: coalesced atomics)
-#pragma unroll
-        for (int v = 0; v < 16; v++) {
-            const int row = row0 + 8 * (v / 4) + 4 * hf + (v % 4);
-            if (row < n_rows) {
-                float* dst = p.dq_acc + ((q_base + row) * p.Hq + h) * D + l32;
-#pragma unroll
-                for (int db = 0; db < NDB; db++) atomicAdd(dst + db * 32, dQ[db][v] * p.scale);
-            }
-        }
+        if (u + 1 < n_units) store_unit((u + 1) & 1);
+        __syncthreads();
     }
 
-    // sum dK / dV over the waves through LDS, then write bf16 rows of the history keys
-    __syncthreads();  // all waves are done with their private regions
-    float* red = (float*)wave_base;
-#pragma unroll 1
-    for (int which = 0; which < 2; which++) {
-        for (int i = tid; i < BN * D; i += NT) red[i] = 0.f;
-        __syncthreads();
+    // write the wave's 32 key rows: lanes cover 32 consecutive d
+    if (wave_live) {
+        __bf16* dkg = (__bf16*)p.dk;
+        __bf16* dvg = (__bf16*)p.dv;
 #pragma unroll
-        for (int kb = 0; kb < NKB; kb++)
+        for (int v = 0; v < 16; v++) {
+            const int key = kw + 8 * (v / 4) + 4 * hf + (v % 4);
+            if (key < L) {
+                const int64_t off = ((kv_base + key) * p.Hkv + g) * D + l32;
 #pragma unroll
-            for (int db = 0; db < NDB; db++)
-#pragma unroll
-                for (int v = 0; v < 16; v++) {
-                    const int key = kb * 32 + 8 * (v / 4) + 4 * hf + (v % 4);
-                    const float val = which == 0 ? dK[kb][db][v] * p.scale : dV[kb][db][v];
-                    atomicAdd(red + key * D + db * 32 + l32, val);
+                for (int db = 0; db < NDB; db++) {
+                    dkg[off + db * 32] = (__bf16)(dK[db][v] * p.scale);
+                    dvg[off + db * 32] = (__bf16)dV[db][v];
                 }
-        __syncthreads();
-        __bf16* dst = (__bf16*)(which == 0 ? p.dk : p.dv);
-        for (int c = tid; c < NCH; c += NT) {
-            const int key = c / CPR, dc = c % CPR;
-            if (key0 + key < L) {
-                bf16x8 o;
-#pragma unroll
-                for (int j = 0; j < 8; j++) o[j] = (__bf16)red[key * D + dc * 8 + j];
-                *(bf16x8*)(dst + ((kv_base + key0 + key) * p.Hkv + g) * D + dc * 8) = o;
             }
         }
-        __syncthreads();
     }
 }
 
-template <int D, int BN, int NW>
-hipError_t launch_main(const Params& p, hipStream_t s) {
-    using SM = BwdSmem<D, BN, NW>;
+int gcd_i(int a, int b) { return b == 0 ? a : gcd_i(b, a % b); }
+
+template <int D, int RB, int NW>
+hipError_t launch_dq(const Params& p, hipStream_t s) {
+    const int r = p.Hq / p.Hkv;
+    const int hpb = gcd_i(r, NW);
+    const int n_hc = r / hpb;
+    const int BM = (NW / hpb) * RB * 32;
+    const int64_t rows = max_query_rows(p);
+    if (rows <= 0) return hipSuccess;
+    if ((int64_t)p.Hkv * n_hc > 65535) return hipErrorInvalidValue;
+    dim3 grid((unsigned)((rows + BM - 1) / BM), (unsigned)(p.Hkv * n_hc), (unsigned)p.batch);
+    hipLaunchKernelGGL((bwd_dq_kernel<D, RB, NW>), grid, dim3(NW * 64), 0, s, p, hpb, n_hc);
+    return hipGetLastError();
+}
+
+template <int D, int NW>
+hipError_t launch_dkdv(const Params& p, hipStream_t s) {
     if (p.max_hist <= 0) return hipSuccess;
-    static bool configured = false;  // raising the dynamic LDS limit is a per-function, process-wide setting
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute((const void*)bwd_main_kernel<D, BN, NW>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)SM::BYTES);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
-    dim3 grid((unsigned)((p.max_hist + BN - 1) / BN), (unsigned)p.Hkv, (unsigned)p.batch);
-    hipLaunchKernelGGL((bwd_main_kernel<D, BN, NW>), grid, dim3(NW * 64), SM::BYTES, s, p);
+    dim3 grid((unsigned)((p.max_hist + NW * 32 - 1) / (NW * 32)), (unsigned)p.Hkv, (unsigned)p.batch);
+    hipLaunchKernelGGL((bwd_dkdv_kernel<D, NW>), grid, dim3(NW * 64), 0, s, p);
     return hipGetLastError();
 }
 
@@ -383,23 +526,22 @@ hipError_t launch_bwd_bf16(const Params& p, hipStream_t s) {
     }
     timing_end(MTFM_HTA_KERNEL_BWD_PRE, s);
     if (e != hipSuccess) return e;
-    timing_begin(MTFM_HTA_KERNEL_BWD_MAIN, s);
+    const bool wide = ((p.Hq / p.Hkv) % 8) == 0;
+    timing_begin(MTFM_HTA_KERNEL_BWD_DQ, s);
     switch (p.d) {
-        case 32: e = launch_main<32, 64, 4>(p, s); break;
-        case 64: e = launch_main<64, 64, 4>(p, s); break;
-        default: e = launch_main<128, 32, 4>(p, s); break;
+        case 32: e = wide ? launch_dq<32, 2, 8>(p, s) : launch_dq<32, 2, 4>(p, s); break;
+        case 64: e = wide ? launch_dq<64, 1, 8>(p, s) : launch_dq<64, 2, 4>(p, s); break;
+        default: e = wide ? launch_dq<128, 1, 8>(p, s) : launch_dq<128, 1, 4>(p, s); break;
     }
-    timing_end(MTFM_HTA_KERNEL_BWD_MAIN, s);
+    timing_end(MTFM_HTA_KERNEL_BWD_DQ, s);
     if (e != hipSuccess) return e;
-    const int64_t n8 = p.total_q * p.Hq * p.d / 8;
-    if (n8 > 0) {
-        int64_t blocks = (n8 + 255) / 256;
-        if (blocks > 8192) blocks = 8192;
-        timing_begin(MTFM_HTA_KERNEL_BWD_POST, s);
-        hipLaunchKernelGGL(bwd_post_kernel, dim3((unsigned)blocks), dim3(256), 0, s, p.dq_acc, (__bf16*)p.dq, n8);
-        e = hipGetLastError();
-        timing_end(MTFM_HTA_KERNEL_BWD_POST, s);
+    timing_begin(MTFM_HTA_KERNEL_BWD_DKDV, s);
+    switch (p.d) {
+        case 32: e = launch_dkdv<32, 4>(p, s); break;
+        case 64: e = launch_dkdv<64, 4>(p, s); break;
+        default: e = launch_dkdv<128, 4>(p, s); break;
     }
+    timing_end(MTFM_HTA_KERNEL_BWD_DKDV, s);
     return e;
 }
 

@@ -32,9 +32,6 @@ struct Params {
     int32_t layer;        // 0 full (queries = all tokens), 1 target (queries = target tokens)
     // carved out of the caller's workspace (bwd)
     float* delta;         // [Hq][total_q]   <dout_i, out_i>
-    float* dq_acc;        // [total_q][Hq][d] float32 accumulator (bf16 path)
-    float* dk_acc;        // [total_kv][Hkv][d] float32 accumulator for the self-key terms (bf16 path)
-    float* dv_acc;
 };
 
 // number of query rows a user can have at most, from the host-known bounds

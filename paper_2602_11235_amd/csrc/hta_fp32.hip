@@ -210,9 +210,9 @@ hipError_t launch_bwd_fp32(const Params& p, hipStream_t s) {
     if (e != hipSuccess) return e;
     e = launch_zero_words(p.dv, (size_t)p.total_kv * p.Hkv * p.d, s);
     if (e != hipSuccess) return e;
-    timing_begin(MTFM_HTA_KERNEL_BWD_MAIN, s);
+    timing_begin(MTFM_HTA_KERNEL_BWD_DQ, s);
     e = dispatch(p, s, true);
-    timing_end(MTFM_HTA_KERNEL_BWD_MAIN, s);
+    timing_end(MTFM_HTA_KERNEL_BWD_DQ, s);
     return e;
 }
 
