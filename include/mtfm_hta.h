@@ -65,6 +65,9 @@ enum { MTFM_HTA_LAYER_FULL = 0, MTFM_HTA_LAYER_TARGET = 1 };
 
 /*
  * Bytes of device workspace a call with these sizes needs (0 is possible).  Pure host arithmetic.
+ * The bf16 path keeps there the user schedule it builds on the device at the start of every call
+ * (users ordered by decreasing number of attention tiles, from hist_len / n_targets) and, for the
+ * backward pass, delta = <dout, out> per query row.
  * is_bwd = 0 for mtfm_hta_fwd, 1 for mtfm_hta_bwd.  Returns (size_t)-1 for invalid arguments.
  * The workspace must be 256-byte aligned; its contents are undefined before and after a call and it
  * may be reused by the next call on the same stream.
@@ -85,6 +88,7 @@ MTFM_HTA_API size_t mtfm_hta_workspace_bytes(int layer, int dtype, int is_bwd, i
  *   max_hist, max_targets  host-known upper bounds of hist_len[] / n_targets[] (they size the launch)
  *   softmax_scale          > 0, finite; typically 1/sqrt(head_dim)
  * Data pointers must be 16-byte aligned.  batch == 0 or total_q == 0 is a successful no-op.
+ * workspace: mtfm_hta_workspace_bytes(..., is_bwd = 0, ...) bytes, 256-byte aligned (none for fp32).
  */
 MTFM_HTA_API int mtfm_hta_fwd(const void* q, const void* k, const void* v, void* out, float* lse,
                  const int32_t* q_offsets, const int32_t* kv_offsets, const int32_t* hist_len,

@@ -22,19 +22,30 @@ int fail(int code, const char* fmt, ...) {
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Workspace {
-    size_t delta_off, total;
+    size_t order_off, delta_off, total;
 };
 
-// Layout of the caller's workspace.  Forward needs none.  Backward (bf16): delta [Hq][total_q] f32.
-// Backward (fp32): delta is computed inside the row kernel; nothing needed.
-Workspace plan_workspace(int dtype, int is_bwd, int64_t total_q, int64_t total_kv, int32_t Hq, int32_t Hkv,
-                         int32_t d) {
-    (void)total_kv; (void)Hkv; (void)d;
-    Workspace w{0, 0};
-    if (!is_bwd || dtype == MTFM_HTA_FP32) return w;
-    w.delta_off = 0;
-    w.total = align256((size_t)total_q * Hq * sizeof(float));
+// Layout of the caller's workspace (bf16 path; the fp32 debug path needs none):
+//   order [batch] int32   users by decreasing tile count, rebuilt by every call
+//   delta [Hq][total_q] f32   backward only
+Workspace plan_workspace(int dtype, int is_bwd, int32_t batch, int64_t total_q, int32_t Hq) {
+    Workspace w{0, 0, 0};
+    if (dtype == MTFM_HTA_FP32) return w;
+    w.order_off = 0;
+    w.total = hta::schedule_bytes(batch);
+    if (is_bwd) {
+        w.delta_off = w.total;
+        w.total += align256((size_t)total_q * Hq * sizeof(float));
+    }
     return w;
+}
+
+int check_workspace(const Workspace& w, const void* workspace, size_t workspace_bytes) {
+    if (w.total == 0) return MTFM_HTA_OK;
+    if (!workspace || workspace_bytes < w.total)
+        return fail(MTFM_HTA_ERR_WORKSPACE, "this call needs %zu bytes of workspace, got %zu", w.total, workspace_bytes);
+    if (((uintptr_t)workspace & 255u) != 0) return fail(MTFM_HTA_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+    return MTFM_HTA_OK;
 }
 
 int check_scalars(int layer, int dtype, int32_t batch, int64_t total_q, int64_t total_kv, int32_t max_hist,
@@ -77,7 +88,7 @@ size_t mtfm_hta_workspace_bytes(int layer, int dtype, int is_bwd, int32_t batch,
                                 int32_t max_hist, int32_t max_targets, int32_t Hq, int32_t Hkv, int32_t head_dim) {
     if (check_scalars(layer, dtype, batch, total_q, total_kv, max_hist, max_targets, Hq, Hkv, head_dim) != MTFM_HTA_OK)
         return (size_t)-1;
-    return plan_workspace(dtype, is_bwd, total_q, total_kv, Hq, Hkv, head_dim).total;
+    return plan_workspace(dtype, is_bwd, batch, total_q, Hq).total;
 }
 
 int mtfm_hta_validate_host(const int32_t* q_offsets, const int32_t* kv_offsets, const int32_t* hist_len,
@@ -121,15 +132,22 @@ int mtfm_hta_fwd(const void* q, const void* k, const void* v, void* out, float* 
         return fail(MTFM_HTA_ERR_INVALID_ARG, "null pointer argument");
     if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out))
         return fail(MTFM_HTA_ERR_INVALID_ARG, "q, k, v, out must be 16-byte aligned");
-    (void)workspace;
-    (void)workspace_bytes;  // the forward pass needs no workspace
+    const Workspace w = plan_workspace(dtype, 0, batch, total_q, Hq);
+    rc = check_workspace(w, workspace, workspace_bytes);
+    if (rc != MTFM_HTA_OK) return rc;
     hta::Params p{};
     p.q = q; p.k = k; p.v = v; p.out = out; p.lse = lse;
     p.q_off = q_offsets; p.kv_off = kv_offsets; p.hist_len = hist_len; p.n_targets = n_targets;
     p.batch = batch; p.total_q = total_q; p.total_kv = total_kv; p.max_hist = max_hist; p.max_targets = max_targets;
     p.Hq = Hq; p.Hkv = Hkv; p.d = head_dim; p.scale = softmax_scale; p.layer = layer;
     hipStream_t s = (hipStream_t)stream;
-    hipError_t e = dtype == MTFM_HTA_FP32 ? hta::launch_fwd_fp32(p, s) : hta::launch_fwd_bf16(p, s);
+    hipError_t e = hipSuccess;
+    if (dtype == MTFM_HTA_BF16) {
+        int32_t* order = (int32_t*)((char*)workspace + w.order_off);
+        e = hta::launch_schedule(p, order, s);
+        p.order = order;
+    }
+    if (e == hipSuccess) e = dtype == MTFM_HTA_FP32 ? hta::launch_fwd_fp32(p, s) : hta::launch_fwd_bf16(p, s);
     if (e != hipSuccess) return fail(MTFM_HTA_ERR_LAUNCH, "forward launch failed: %s", hipGetErrorString(e));
     return MTFM_HTA_OK;
 }
@@ -149,12 +167,9 @@ int mtfm_hta_bwd(const void* dout, const void* q, const void* k, const void* v, 
     if (misaligned(dout) || misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out) || misaligned(dq) ||
         misaligned(dk) || misaligned(dv))
         return fail(MTFM_HTA_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
-    const Workspace w = plan_workspace(dtype, 1, total_q, total_kv, Hq, Hkv, head_dim);
-    if (w.total > 0) {
-        if (!workspace || workspace_bytes < w.total)
-            return fail(MTFM_HTA_ERR_WORKSPACE, "backward needs %zu bytes of workspace, got %zu", w.total, workspace_bytes);
-        if (((uintptr_t)workspace & 255u) != 0) return fail(MTFM_HTA_ERR_WORKSPACE, "workspace must be 256-byte aligned");
-    }
+    const Workspace w = plan_workspace(dtype, 1, batch, total_q, Hq);
+    rc = check_workspace(w, workspace, workspace_bytes);
+    if (rc != MTFM_HTA_OK) return rc;
     hta::Params p{};
     p.dout = dout; p.q = q; p.k = k; p.v = v; p.out = const_cast<void*>(out); p.lse = const_cast<float*>(lse);
     p.dq = dq; p.dk = dk; p.dv = dv;
@@ -166,7 +181,13 @@ int mtfm_hta_bwd(const void* dout, const void* q, const void* k, const void* v, 
         p.delta = (float*)(base + w.delta_off);
     }
     hipStream_t s = (hipStream_t)stream;
-    hipError_t e = dtype == MTFM_HTA_FP32 ? hta::launch_bwd_fp32(p, s) : hta::launch_bwd_bf16(p, s);
+    hipError_t e = hipSuccess;
+    if (dtype == MTFM_HTA_BF16) {
+        int32_t* order = (int32_t*)((char*)workspace + w.order_off);
+        e = hta::launch_schedule(p, order, s);
+        p.order = order;
+    }
+    if (e == hipSuccess) e = dtype == MTFM_HTA_FP32 ? hta::launch_bwd_fp32(p, s) : hta::launch_bwd_bf16(p, s);
     if (e != hipSuccess) return fail(MTFM_HTA_ERR_LAUNCH, "backward launch failed: %s", hipGetErrorString(e));
     return MTFM_HTA_OK;
 }

@@ -43,7 +43,7 @@ template <int D>
 __global__ __launch_bounds__(256) void bwd_pre_kernel(Params p) {
     constexpr int LPR = D / 8;           // lanes per item, 8 elements (16 bytes) each
     constexpr int IPB = 256 / LPR;       // items per block
-    const int b = blockIdx.z;
+    const int b = blockIdx.z;  // bandwidth-bound pass: user order does not matter
     const int L = p.hist_len[b], T = p.n_targets[b];
     const int n_rows = p.layer == 0 ? L + T : T;
     const int r = p.Hq / p.Hkv;
@@ -129,7 +129,7 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(Params p, int hpb, i
     __shared__ __attribute__((aligned(16))) __bf16 smem[2 * BUF_ELEMS];
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
-    const int b = blockIdx.z;
+    const int b = scheduled_user(p, blockIdx.z);
     const int g = blockIdx.y / n_hc, hc = blockIdx.y % n_hc;
     const int L = p.hist_len[b], T = p.n_targets[b];
     const int n_rows = p.layer == 0 ? L + T : T;
@@ -313,11 +313,14 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(Params p, int hpb, i
 }
 
 // ---------------------------------------------------------------------------------------- dK, dV
+constexpr int UPI = 2;  // (head, 32-row block) units staged and consumed per loop iteration of the dK/dV kernel
+
 template <int D, int NW>
 struct DkdvSmem {
     static constexpr int QS = D + 8;                    // Q/dO tile row pitch (elements)
     static constexpr int TILE = 32 * QS;                // one 32-row tile
-    static constexpr size_t BUF_BYTES = (size_t)2 * TILE * 2 + 2 * 32 * sizeof(float);  // Q, dO, lse2[32], delta[32]
+    static constexpr size_t UNIT_BYTES = (size_t)2 * TILE * 2 + 2 * 32 * sizeof(float);  // Q, dO, lse2[32], delta[32]
+    static constexpr size_t BUF_BYTES = UPI * UNIT_BYTES;
     static constexpr size_t BYTES = 2 * BUF_BYTES;      // double buffered
 };
 
@@ -326,12 +329,13 @@ template <int D, int NW>
 __global__ __launch_bounds__(NW * 64, 2) void bwd_dkdv_kernel(Params p) {
     using SM = DkdvSmem<D, NW>;
     constexpr int NT = NW * 64, QS = SM::QS;
-    constexpr int CPR = D / 8, NCH = 32 * CPR, CH = (NCH + NT - 1) / NT;
+    constexpr int CPR = D / 8, NCH = UPI * 32 * CPR, CH = (NCH + NT - 1) / NT;
     constexpr int NKS = D / 16, NDB = D / 32;
+    static_assert(NT >= UPI * 64, "one lane per lse/delta value");
     __shared__ __attribute__((aligned(16))) unsigned char smem_raw[SM::BYTES];
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
-    const int b = blockIdx.z, g = blockIdx.y;
+    const int b = scheduled_user(p, blockIdx.z), g = blockIdx.y;
     const int L = p.hist_len[b], T = p.n_targets[b];
     const int key0 = blockIdx.x * (NW * 32);
     if (key0 >= L) return;  // uniform: this key tile does not exist for the user
@@ -343,6 +347,7 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dkdv_kernel(Params p) {
     const int kw = key0 + wave * 32;        // first key of this wave
     const bool wave_live = kw < L;          // a wave past the history only helps staging
     const bool key_live = kw + l32 < L;
+    const bool wave_ragged = kw + 32 > L;
 
     // stationary operands: K and V rows of the wave's keys (B operand of S = Q K^T and dP = dO V^T)
     bf16x8 kf[NKS], vf[NKS];
@@ -366,96 +371,132 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dkdv_kernel(Params p) {
 
     const int n_rb = (n_rows + 31) / 32;
     const int n_units = n_rb * r;  // unit u = (32-row block u / r, head g*r + u % r)
+    const int n_iter = (n_units + UPI - 1) / UPI;
     uint4 qreg[CH], doreg[CH];
-    float sreg = 0.f;  // lane < 32 of wave 0: lse2 of row `lane`; lanes 32..63 of wave 0: delta of row lane-32
-    auto load_unit = [&](int u) {
-        const int row0 = (u / r) * 32, h = g * r + u % r;
-#pragma unroll
-        for (int i = 0; i < CH; i++) {
+    float sreg = 0.f;  // threads 0..64*UPI-1: lse2 (first 32 of each 64) or delta (last 32) of one row of one unit
+    auto load_units = [&](int it) {
+        static_for<0, CH>([&](auto I) {
+            constexpr int i = decltype(I)::value;
             const int c = tid + i * NT;
+            qreg[i] = make_uint4(0, 0, 0, 0);
+            doreg[i] = make_uint4(0, 0, 0, 0);
             if (c < NCH) {
-                int row = row0 + c / CPR;
+                int u = it * UPI + c / (32 * CPR);
+                u = u < n_units ? u : n_units - 1;  // a missing unit repeats the last one and is not consumed
+                const int cc = c % (32 * CPR);
+                int row = (u / r) * 32 + cc / CPR;
                 row = row < n_rows ? row : n_rows - 1;
-                const int64_t off = ((q_base + row) * p.Hq + h) * D + (c % CPR) * 8;
+                const int64_t off = ((q_base + row) * p.Hq + g * r + u % r) * D + (cc % CPR) * 8;
                 qreg[i] = *(const uint4*)((const __bf16*)p.q + off);
                 doreg[i] = *(const uint4*)((const __bf16*)p.dout + off);
             }
-        }
-        if (tid < 64) {
-            const int row = row0 + (tid & 31);
+        });
+        if (tid < 64 * UPI) {
+            int u = it * UPI + tid / 64;
+            u = u < n_units ? u : n_units - 1;
+            const int row = (u / r) * 32 + (tid & 31);
             const bool live = row < n_rows;
-            const int64_t idx = (int64_t)h * p.total_q + q_base + (live ? row : n_rows - 1);
+            const int64_t idx = (int64_t)(g * r + u % r) * p.total_q + q_base + (live ? row : n_rows - 1);
             // rows past the end get lse = +inf, i.e. P = 0
-            sreg = tid < 32 ? (live ? p.lse[idx] * LOG2E : INFINITY) : p.delta[idx];
+            sreg = (tid & 32) == 0 ? (live ? p.lse[idx] * LOG2E : INFINITY) : p.delta[idx];
         }
     };
-    auto store_unit = [&](int buf) {
-        __bf16* Qd = (__bf16*)(smem_raw + buf * SM::BUF_BYTES);
-        __bf16* dOd = Qd + SM::TILE;
-        float* sd = (float*)(dOd + SM::TILE);
-#pragma unroll
-        for (int i = 0; i < CH; i++) {
+    auto store_units = [&](int buf) {
+        unsigned char* base = smem_raw + buf * SM::BUF_BYTES;
+        static_for<0, CH>([&](auto I) {
+            constexpr int i = decltype(I)::value;
             const int c = tid + i * NT;
             if (c < NCH) {
-                *(uint4*)(Qd + (c / CPR) * QS + (c % CPR) * 8) = qreg[i];
-                *(uint4*)(dOd + (c / CPR) * QS + (c % CPR) * 8) = doreg[i];
+                const int cc = c % (32 * CPR);
+                __bf16* Qd = (__bf16*)(base + (c / (32 * CPR)) * SM::UNIT_BYTES);
+                *(uint4*)(Qd + (cc / CPR) * QS + (cc % CPR) * 8) = qreg[i];
+                *(uint4*)(Qd + SM::TILE + (cc / CPR) * QS + (cc % CPR) * 8) = doreg[i];
+            }
+        });
+        if (tid < 64 * UPI) ((float*)(base + (tid / 64) * SM::UNIT_BYTES + (size_t)4 * SM::TILE))[tid & 63] = sreg;
+    };
+    // one (head, 32-row block) unit against the wave's 32 keys
+    auto unit = [&](const unsigned char* ubase, auto ragged) {
+        const __bf16* Qs = (const __bf16*)ubase;
+        const __bf16* dOs = Qs + SM::TILE;
+        const float* ss = (const float*)(dOs + SM::TILE);
+        // all LDS operands are requested up front, in the order they are consumed: their latency then hides
+        // behind the MFMAs and the exponentials instead of stalling each product
+        bf16x8 qa[NKS], da[NKS];
+#pragma unroll
+        for (int ks = 0; ks < NKS; ks++) {
+            qa[ks] = *(const bf16x8*)(Qs + l32 * QS + ks * 16 + 8 * hf);
+            da[ks] = *(const bf16x8*)(dOs + l32 * QS + ks * 16 + 8 * hf);
+        }
+        floatx4 l4[4], d4[4];  // registers 4j..4j+3 hold rows 8j+4hf .. 8j+4hf+3
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            l4[j] = *(const floatx4*)(ss + 8 * j + 4 * hf);
+            d4[j] = *(const floatx4*)(ss + 32 + 8 * j + 4 * hf);
+        }
+        floatx16 S, dP;  // [row (registers)][key (lanes)]
+#pragma unroll
+        for (int ks = 0; ks < NKS; ks++) {
+            if (ks == 0) {
+                const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                S = mfma32(qa[ks], kf[ks], zero);
+                dP = mfma32(da[ks], vf[ks], zero);
+            } else {
+                S = mfma32(qa[ks], kf[ks], S);
+                dP = mfma32(da[ks], vf[ks], dP);
             }
         }
-        if (tid < 64) sd[tid] = sreg;
+        bf16x8 dot[NDB][2], qt[NDB][2];
+#pragma unroll
+        for (int db = 0; db < NDB; db++)
+#pragma unroll
+            for (int s2 = 0; s2 < 2; s2++) {
+                dot[db][s2] = lds_read_tr_8(dOs, QS, 16 * s2 + 4 * hf, db * 32 + dhalf16, lane);
+                qt[db][s2] = lds_read_tr_8(Qs, QS, 16 * s2 + 4 * hf, db * 32 + dhalf16, lane);
+            }
+        bf16x8 pb[2], dsb[2];
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+#pragma unroll
+            for (int e = 0; e < 4; e++) {
+                const int v = 4 * j + e;
+                float pw = fast_exp2(fmaf(S[v], c2, -l4[j][e]));
+                if (decltype(ragged)::value) pw = key_live ? pw : 0.f;  // keys past the history carry no weight
+                pb[v / 8][v % 8] = (__bf16)pw;
+                dsb[v / 8][v % 8] = (__bf16)(pw * (dP[v] - d4[j][e]));
+            }
+        }
+        // dV[key][d] += P^T[key][row] dO[row][d];  dK[key][d] += dS^T[key][row] Q[row][d]
+#pragma unroll
+        for (int db = 0; db < NDB; db++)
+#pragma unroll
+            for (int s2 = 0; s2 < 2; s2++) {
+                dV[db] = mfma32(pb[s2], dot[db][s2], dV[db]);
+                dK[db] = mfma32(dsb[s2], qt[db][s2], dK[db]);
+            }
     };
 
-    if (n_units > 0) {
-        load_unit(0);
-        store_unit(0);
+    if (n_iter > 0) {
+        load_units(0);
+        store_units(0);
     }
     __syncthreads();
     wait_vmem_loads();
-    for (int u = 0; u < n_units; u++) {
-        const __bf16* Qs = (const __bf16*)(smem_raw + (u & 1) * SM::BUF_BYTES);
-        const __bf16* dOs = Qs + SM::TILE;
-        const float* ss = (const float*)(dOs + SM::TILE);
-        if (u + 1 < n_units) load_unit(u + 1);
+    for (int it = 0; it < n_iter; it++) {
+        const unsigned char* base = smem_raw + (it & 1) * SM::BUF_BYTES;
+        if (it + 1 < n_iter) load_units(it + 1);
         if (wave_live) {
-            floatx16 S, dP;  // [row (registers)][key (lanes)]
 #pragma unroll
-            for (int ks = 0; ks < NKS; ks++) {
-                const bf16x8 qa = *(const bf16x8*)(Qs + l32 * QS + ks * 16 + 8 * hf);
-                const bf16x8 da = *(const bf16x8*)(dOs + l32 * QS + ks * 16 + 8 * hf);
-                if (ks == 0) {
-                    const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-                    S = mfma32(qa, kf[ks], zero);
-                    dP = mfma32(da, vf[ks], zero);
-                } else {
-                    S = mfma32(qa, kf[ks], S);
-                    dP = mfma32(da, vf[ks], dP);
+            for (int uu = 0; uu < UPI; uu++) {
+                if (it * UPI + uu < n_units) {
+                    if (wave_ragged)
+                        unit(base + uu * SM::UNIT_BYTES, std::true_type{});
+                    else
+                        unit(base + uu * SM::UNIT_BYTES, std::false_type{});
                 }
             }
-            bf16x8 pb[2], dsb[2];
-#pragma unroll
-            for (int j = 0; j < 4; j++) {  // registers 4j..4j+3 hold rows 8j+4hf .. 8j+4hf+3
-                const floatx4 l4 = *(const floatx4*)(ss + 8 * j + 4 * hf);
-                const floatx4 d4 = *(const floatx4*)(ss + 32 + 8 * j + 4 * hf);
-#pragma unroll
-                for (int e = 0; e < 4; e++) {
-                    const int v = 4 * j + e;
-                    float pw = fast_exp2(fmaf(S[v], c2, -l4[e]));
-                    pw = key_live ? pw : 0.f;
-                    pb[v / 8][v % 8] = (__bf16)pw;
-                    dsb[v / 8][v % 8] = (__bf16)(pw * (dP[v] - d4[e]));
-                }
-            }
-            // dV[key][d] += P^T[key][row] dO[row][d];  dK[key][d] += dS^T[key][row] Q[row][d]
-#pragma unroll
-            for (int db = 0; db < NDB; db++)
-#pragma unroll
-                for (int s2 = 0; s2 < 2; s2++) {
-                    const bf16x8 dot = lds_read_tr_8(dOs, QS, 16 * s2 + 4 * hf, db * 32 + dhalf16, lane);
-                    const bf16x8 qt = lds_read_tr_8(Qs, QS, 16 * s2 + 4 * hf, db * 32 + dhalf16, lane);
-                    dV[db] = mfma32(pb[s2], dot, dV[db]);
-                    dK[db] = mfma32(dsb[s2], qt, dK[db]);
-                }
         }
-        if (u + 1 < n_units) store_unit((u + 1) & 1);
+        if (it + 1 < n_iter) store_units((it + 1) & 1);
         __syncthreads();
     }
 

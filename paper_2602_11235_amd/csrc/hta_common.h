@@ -32,6 +32,7 @@ struct Params {
     int32_t layer;        // 0 full (queries = all tokens), 1 target (queries = target tokens)
     // carved out of the caller's workspace (bwd)
     float* delta;         // [Hq][total_q]   <dout_i, out_i>
+    const int32_t* order; // [batch] users by decreasing tile count (bf16 path), or null = identity
 };
 
 // number of query rows a user can have at most, from the host-known bounds
@@ -48,6 +49,10 @@ bool bf16_supported(int32_t d, int32_t Hq, int32_t Hkv);
 // MTFM_HTA_KERNEL_* values
 void timing_begin(int kind, hipStream_t s);
 void timing_end(int kind, hipStream_t s);
+// user order of the launch (blockIdx.z -> user): long histories first
+size_t schedule_bytes(int32_t batch);
+hipError_t launch_schedule(const Params& p, int32_t* order, hipStream_t s);
+__device__ inline int scheduled_user(const Params& p, int slot) { return p.order ? p.order[slot] : slot; }
 // fill `n` 32-bit words with zero (a kernel, so that a caller may capture the call in a HIP graph)
 hipError_t launch_zero_words(void* ptr, size_t n_words, hipStream_t s);
 

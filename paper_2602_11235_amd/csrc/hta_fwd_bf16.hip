@@ -44,7 +44,7 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb,
     __shared__ __attribute__((aligned(16))) __bf16 smem[Tile<D>::LDS_ELEMS];
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
-    const int b = blockIdx.z;
+    const int b = scheduled_user(p, blockIdx.z);
     const int g = blockIdx.y / n_hc, hc = blockIdx.y % n_hc;
     const int L = p.hist_len[b], T = p.n_targets[b];
     const int n_rows = p.layer == 0 ? L + T : T;

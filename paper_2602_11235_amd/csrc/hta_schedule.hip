@@ -1,0 +1,82 @@
+// Work schedule of a jagged batch, built on the device from hist_len / n_targets (no host round trip).
+//
+// Under the hybrid mask (rules 1 and 3, Section 3.2.2) user b owns exactly the tiles
+// (query rows) x (history keys): rows = L_b + T_b in a full layer, T_b in a target layer, keys = L_b;
+// nothing else is ever issued (the self key of a target row is a per-row term).  The attention
+// kernels enumerate those tiles from (L_b, T_b) themselves; what the schedule adds is the ORDER of
+// the users: workgroups are dispatched user-major, so listing users by decreasing tile count
+// (rows x keys) starts the long-history users first and leaves the short ones to fill the tail.
+#include "hta_common.h"
+
+namespace hta {
+namespace {
+
+constexpr int SCHED_THREADS = 1024;
+constexpr int RANK_SORT_MAX = 4096;   // exact, deterministic rank sort up to this many users
+constexpr int N_BUCKETS = 2048;       // bucketed counting sort above it
+
+__device__ inline float user_cost(const Params& p, int b) {
+    const float L = (float)p.hist_len[b], T = (float)p.n_targets[b];
+    return (p.layer == 0 ? L + T : T) * L;
+}
+
+// order[i] = user with the i-th largest cost; ties broken by user index, so the result is unique
+__global__ __launch_bounds__(SCHED_THREADS) void schedule_rank_kernel(Params p, int32_t* order) {
+    __shared__ float cost[RANK_SORT_MAX];
+    const int B = p.batch;
+    for (int b = threadIdx.x; b < B; b += SCHED_THREADS) cost[b] = user_cost(p, b);
+    __syncthreads();
+    for (int b = threadIdx.x; b < B; b += SCHED_THREADS) {
+        const float c = cost[b];
+        int rank = 0;
+        for (int o = 0; o < B; o++) {
+            const float co = cost[o];  // same address for the whole wave: an LDS broadcast
+            rank += (co > c || (co == c && o < b)) ? 1 : 0;
+        }
+        order[rank] = b;
+    }
+}
+
+// Large batches: users fall into N_BUCKETS cost classes (by cost / max possible cost); classes are laid out
+// by decreasing cost, users inside a class in arrival order of the atomics (any order is a valid schedule).
+__global__ __launch_bounds__(SCHED_THREADS) void schedule_bucket_kernel(Params p, int32_t* order) {
+    __shared__ int count[N_BUCKETS];
+    __shared__ int start[N_BUCKETS];
+    const int B = p.batch;
+    const float rows_max = (float)(p.layer == 0 ? (int64_t)p.max_hist + p.max_targets : (int64_t)p.max_targets);
+    const float inv = (float)(N_BUCKETS - 1) / fmaxf(rows_max * (float)p.max_hist, 1.f);
+    for (int i = threadIdx.x; i < N_BUCKETS; i += SCHED_THREADS) count[i] = 0;
+    __syncthreads();
+    for (int b = threadIdx.x; b < B; b += SCHED_THREADS) {
+        const int k = min(N_BUCKETS - 1, max(0, (int)(user_cost(p, b) * inv)));
+        atomicAdd(&count[N_BUCKETS - 1 - k], 1);  // bucket 0 = most expensive class
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int acc = 0;
+        for (int i = 0; i < N_BUCKETS; i++) {
+            start[i] = acc;
+            acc += count[i];
+        }
+    }
+    __syncthreads();
+    for (int b = threadIdx.x; b < B; b += SCHED_THREADS) {
+        const int k = min(N_BUCKETS - 1, max(0, (int)(user_cost(p, b) * inv)));
+        order[atomicAdd(&start[N_BUCKETS - 1 - k], 1)] = b;
+    }
+}
+
+}  // namespace
+
+size_t schedule_bytes(int32_t batch) { return (((size_t)batch * sizeof(int32_t)) + 255) & ~(size_t)255; }
+
+hipError_t launch_schedule(const Params& p, int32_t* order, hipStream_t s) {
+    if (p.batch <= 0) return hipSuccess;
+    if (p.batch <= RANK_SORT_MAX)
+        hipLaunchKernelGGL(schedule_rank_kernel, dim3(1), dim3(SCHED_THREADS), 0, s, p, order);
+    else
+        hipLaunchKernelGGL(schedule_bucket_kernel, dim3(1), dim3(SCHED_THREADS), 0, s, p, order);
+    return hipGetLastError();
+}
+
+}  // namespace hta

@@ -165,6 +165,10 @@ class Batch:
         self.out = torch.empty_like(q)
         self.lse = torch.empty((self.Hq, self.total_q), dtype=torch.float32, device=q.device)
         self.dq = self.dk = self.dv = None
+        self.fwd_workspace_bytes = mtfm_hta_workspace_bytes(self.layer, self.dtype, False, *self._sizes())
+        self.fwd_workspace = None
+        if self.fwd_workspace_bytes:
+            self.fwd_workspace = torch.empty(self.fwd_workspace_bytes, dtype=torch.uint8, device=q.device)
         self.workspace = None
         self.workspace_bytes = 0
 
@@ -174,7 +178,8 @@ class Batch:
 
     def forward(self, stream=None) -> Tuple[torch.Tensor, torch.Tensor]:
         mtfm_hta_fwd(self.q, self.k, self.v, self.out, self.lse, self.q_offsets, self.kv_offsets, self.hist_len,
-                     self.n_targets, *self._sizes(), self.softmax_scale, self.dtype, self.layer, None, 0, stream)
+                     self.n_targets, *self._sizes(), self.softmax_scale, self.dtype, self.layer, self.fwd_workspace,
+                     self.fwd_workspace_bytes, stream)
         return self.out, self.lse
 
     def prepare_backward(self) -> None:

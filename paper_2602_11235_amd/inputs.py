@@ -16,6 +16,7 @@ from __future__ import annotations
 
 import dataclasses
 import math
+import os
 from typing import Dict, Optional
 
 import numpy as np
@@ -54,12 +55,16 @@ def uniform01(key: np.uint64, start: int, n: int) -> np.ndarray:
     return ((raw_bits(key, start, n) >> np.uint64(11)).astype(np.float64) + 0.5) * (1.0 / 9007199254740992.0)
 
 
-def normal(key: np.uint64, n: int, chunk: int = 1 << 22) -> np.ndarray:
-    """n standard normals (float64) by Box-Muller; element 2i and 2i+1 come from uniform pair i."""
-    out = np.empty(n, dtype=np.float64)
-    pos = 0
-    while pos < n:
+def normal(key: np.uint64, n: int, chunk: int = 1 << 21, dtype=np.float64, scale: float = 1.0) -> np.ndarray:
+    """n standard normals by Box-Muller in float64 (element 2i and 2i+1 come from uniform pair i), times
+    ``scale``, stored as ``dtype``.  The value of an element depends only on (key, index): chunks are
+    independent and are drawn by a few threads."""
+    out = np.empty(n, dtype=dtype)
+    starts = list(range(0, n, chunk))
+
+    def work(pos):
         m = min(chunk, n - pos)
+        tmp = np.empty(m, dtype=np.float64)
         first_pair = pos // 2
         npairs = (pos + m + 1) // 2 - first_pair
         u = uniform01(key, 2 * first_pair, 2 * npairs)
@@ -69,8 +74,18 @@ def normal(key: np.uint64, n: int, chunk: int = 1 << 22) -> np.ndarray:
         z[0::2] = r * np.cos(t)
         z[1::2] = r * np.sin(t)
         off = pos - 2 * first_pair
-        out[pos:pos + m] = z[off:off + m]
-        pos += m
+        tmp[:] = z[off:off + m]
+        if scale != 1.0:
+            tmp *= scale
+        out[pos:pos + m] = tmp
+
+    if len(starts) <= 1:
+        for pos in starts:
+            work(pos)
+    else:
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as ex:
+            list(ex.map(work, starts))
     return out
 
 
@@ -167,7 +182,7 @@ class Case:
 
 def _values(key: np.uint64, shape: tuple, std: float, dtype: str) -> np.ndarray:
     n = int(np.prod(shape)) if len(shape) else 1
-    x = (normal(key, n) * std).astype(np.float32)
+    x = normal(key, n, dtype=np.float32, scale=std)  # scaled in float64, then rounded to float32
     if dtype == "bf16":
         x = bf16_bits_to_f32(f32_to_bf16_bits(x))
     return x.reshape(shape)

@@ -27,7 +27,8 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_workspace_bytes_is_host_arithmetic():
-    assert hta.mtfm_hta_workspace_bytes(hta.LAYER_FULL, hta.BF16, False, 4, 1000, 1000, 512, 64, 8, 2, 64) == 0
+    assert hta.mtfm_hta_workspace_bytes(hta.LAYER_FULL, hta.BF16, False, 4, 1000, 1000, 512, 64, 8, 2, 64) == 256
+    assert hta.mtfm_hta_workspace_bytes(hta.LAYER_FULL, hta.FP32, False, 4, 1000, 1000, 512, 64, 8, 2, 64) == 0
     n = hta.mtfm_hta_workspace_bytes(hta.LAYER_FULL, hta.BF16, True, 4, 1000, 1000, 512, 64, 8, 2, 64)
     assert n >= 1000 * 8 * 4 and n % 256 == 0
     assert hta.mtfm_hta_workspace_bytes(hta.LAYER_FULL, hta.FP32, True, 4, 1000, 1000, 512, 64, 8, 2, 16) == 0

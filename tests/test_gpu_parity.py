@@ -72,3 +72,80 @@ def test_c2_bf16_backward_full_batch():
 def test_c3_bf16_forward_backward_sampled_users():
     c = inputs.make_case(inputs.CONFIGS["C3"])
     check_case(c, with_bwd=True, users=pick_users(c, 2))
+
+
+# ------------------------------------------------------------------------------ remaining workloads
+def test_c4_target_layer_forward_backward_sampled_users():
+    c = inputs.make_case(inputs.CONFIGS["C4"])
+    check_case(c, with_bwd=True, users=[0, 255, 511])
+
+
+def test_c5_long_history_stress_sampled_users():
+    c = inputs.make_case(inputs.CONFIGS["C5"])
+    L = c.hist_len
+    shortest, longest = int(np.argmin(L)), int(np.argmax(L))
+    median = int(np.argsort(L)[len(L) // 2])
+    fewest_t, most_t = int(np.argmin(c.n_targets)), int(np.argmax(c.n_targets))
+    assert L[longest] == 8192, "the recipe puts about 9 % of the users at the cap"
+    say(f"  users: shortest {shortest} (L={L[shortest]}), median {median} (L={L[median]}), longest {longest} "
+        f"(L={L[longest]}, T={c.n_targets[longest]}), fewest/most targets {fewest_t}/{most_t}")
+    # one GPU run, three oracle comparisons; the capped user is checked on one kv group (its 8 query heads)
+    batch = device_batch(c)
+    out, lse = batch.forward()
+    dq, dk, dv = batch.backward(to_torch(c.dout, "bf16"))
+    torch.cuda.synchronize()
+    g = dict(out=host(out), lse=host(lse), dq=host(dq), dk=host(dk), dv=host(dv))
+    from tests.hta_testlib import assert_close, oracle_all
+    for users, kv_group in (([shortest, median, fewest_t], None), ([longest], 1)):
+        ref_case = inputs.take_users(c, users)
+        hs, gs = slice(None), slice(None)
+        if kv_group is not None:
+            r = c.cfg.Hq // c.cfg.Hkv
+            hs, gs = slice(kv_group * r, (kv_group + 1) * r), slice(kv_group, kv_group + 1)
+            ref_case = inputs.take_kv_group(ref_case, kv_group)
+        say(f"    oracle on users {users}, kv group {kv_group} ...")
+        ref = oracle_all(ref_case, True)
+        qrows, kvrows = inputs.user_rows(c.q_offsets, users), inputs.user_rows(c.kv_offsets, users)
+        assert_close("out", g["out"][qrows][:, hs], ref[0], "bf16")
+        assert_close("lse", g["lse"][hs][:, qrows], ref[1], "bf16")
+        assert_close("dq", g["dq"][qrows][:, hs], ref[2], "bf16")
+        assert_close("dk", g["dk"][kvrows][:, gs], ref[3], "bf16")
+        assert_close("dv", g["dv"][kvrows][:, gs], ref[4], "bf16")
+
+
+def test_many_small_users_take_the_bucketed_schedule():
+    # more than 4096 users: the device-side schedule switches from the exact rank sort to cost buckets
+    B = 5000
+    u = inputs.uniform01(inputs.stream_key(5, 7), 0, 2 * B)
+    hist = (u[:B] * 41).astype(np.int32)          # 0 .. 40
+    tgts = (u[B:] * 4).astype(np.int32)           # 0 .. 3
+    c = custom("many_small_users", FULL, hist, tgts, 4, 2, 32, "bf16")
+    check_case(c, with_bwd=True)
+
+
+def test_results_do_not_depend_on_user_order():
+    """The schedule reorders users internally; outputs must be bitwise those of the same users in any batch order."""
+    c = custom("order_a", FULL, [300, 10, 700, 64, 129], [5, 9, 0, 33, 2], 8, 2, 64, "bf16")
+    perm = [2, 4, 0, 3, 1]
+    cp = inputs.take_users(c, perm)
+    ba, bb = device_batch(c), device_batch(cp)
+    oa, la = ba.forward()
+    ob, lb = bb.forward()
+    da = ba.backward(to_torch(c.dout, "bf16"))
+    db = bb.backward(to_torch(cp.dout, "bf16"))
+    torch.cuda.synchronize()
+    qrows, kvrows = inputs.user_rows(c.q_offsets, perm), inputs.user_rows(c.kv_offsets, perm)
+    assert torch.equal(oa[qrows], ob) and torch.equal(la[:, qrows], lb)
+    assert torch.equal(da[0][qrows], db[0]) and torch.equal(da[1][kvrows], db[1]) and torch.equal(da[2][kvrows], db[2])
+
+
+def test_backward_is_bitwise_reproducible():
+    c = inputs.make_case(inputs.CONFIGS["C2"])
+    b = device_batch(c)
+    b.forward()
+    dout = to_torch(c.dout, "bf16")
+    first = [t.clone() for t in b.backward(dout)]
+    second = b.backward(dout)
+    torch.cuda.synchronize()
+    for x, y in zip(first, second):
+        assert torch.equal(x, y)
