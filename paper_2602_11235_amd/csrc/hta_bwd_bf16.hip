@@ -120,7 +120,7 @@ __global__ __launch_bounds__(256) void bwd_pre_kernel(Params p) {
 constexpr int BN = 64;  // keys per LDS tile of the dQ kernel
 
 template <int D, int RB, int NW>
-__global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(Params p, int hpb, int n_hc) {
+__global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(Params p, int hpb, int n_hc, int tpg) {
     constexpr int NT = NW * 64;
     constexpr int KS = D + 8;                      // K/V row pitch (elements)
     constexpr int BUF_ELEMS = 2 * BN * KS;         // one K tile + one V tile
@@ -129,12 +129,14 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(Params p, int hpb, i
     __shared__ __attribute__((aligned(16))) __bf16 smem[2 * BUF_ELEMS];
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
-    const int b = scheduled_user(p, blockIdx.z);
-    const int g = blockIdx.y / n_hc, hc = blockIdx.y % n_hc;
+    const WorkItem w = decode_work(blockIdx.x, p.batch * p.Hkv * n_hc, p.Hkv * n_hc, tpg);
+    if (!w.valid) return;
+    const int b = scheduled_user(p, w.user_slot);
+    const int g = w.y / n_hc, hc = w.y % n_hc;
     const int L = p.hist_len[b], T = p.n_targets[b];
     const int n_rows = p.layer == 0 ? L + T : T;
     const int BM = (NW / hpb) * RB * 32;
-    const int tile_row0 = blockIdx.x * BM;
+    const int tile_row0 = w.tile * BM;
     if (tile_row0 >= n_rows) return;  // uniform for the whole workgroup
     const int r = p.Hq / p.Hkv;
     const int h = g * r + hc * hpb + wave % hpb;
@@ -324,9 +326,9 @@ struct DkdvSmem {
     static constexpr size_t BYTES = 2 * BUF_BYTES;      // double buffered
 };
 
-// grid: x = tile of NW*32 history keys, y = kv head, z = user
+// one workgroup per (user, kv head, tile of NW*32 history keys)
 template <int D, int NW>
-__global__ __launch_bounds__(NW * 64, 2) void bwd_dkdv_kernel(Params p) {
+__global__ __launch_bounds__(NW * 64, 2) void bwd_dkdv_kernel(Params p, int tpg) {
     using SM = DkdvSmem<D, NW>;
     constexpr int NT = NW * 64, QS = SM::QS;
     constexpr int CPR = D / 8, NCH = UPI * 32 * CPR, CH = (NCH + NT - 1) / NT;
@@ -335,9 +337,11 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dkdv_kernel(Params p) {
     __shared__ __attribute__((aligned(16))) unsigned char smem_raw[SM::BYTES];
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
-    const int b = scheduled_user(p, blockIdx.z), g = blockIdx.y;
+    const WorkItem w = decode_work(blockIdx.x, p.batch * p.Hkv, p.Hkv, tpg);
+    if (!w.valid) return;
+    const int b = scheduled_user(p, w.user_slot), g = w.y;
     const int L = p.hist_len[b], T = p.n_targets[b];
-    const int key0 = blockIdx.x * (NW * 32);
+    const int key0 = w.tile * (NW * 32);
     if (key0 >= L) return;  // uniform: this key tile does not exist for the user
     const int n_rows = p.layer == 0 ? L + T : T;
     const int r = p.Hq / p.Hkv;
@@ -529,17 +533,20 @@ hipError_t launch_dq(const Params& p, hipStream_t s) {
     const int BM = (NW / hpb) * RB * 32;
     const int64_t rows = max_query_rows(p);
     if (rows <= 0) return hipSuccess;
-    if ((int64_t)p.Hkv * n_hc > 65535) return hipErrorInvalidValue;
-    dim3 grid((unsigned)((rows + BM - 1) / BM), (unsigned)(p.Hkv * n_hc), (unsigned)p.batch);
-    hipLaunchKernelGGL((bwd_dq_kernel<D, RB, NW>), grid, dim3(NW * 64), 0, s, p, hpb, n_hc);
+    const int64_t n_rt = (rows + BM - 1) / BM;
+    const int64_t n_blocks = work_grid((int64_t)p.batch * p.Hkv * n_hc, n_rt);
+    if (n_blocks >= (1ll << 31)) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((bwd_dq_kernel<D, RB, NW>), dim3((unsigned)n_blocks), dim3(NW * 64), 0, s, p, hpb, n_hc, (int)n_rt);
     return hipGetLastError();
 }
 
 template <int D, int NW>
 hipError_t launch_dkdv(const Params& p, hipStream_t s) {
     if (p.max_hist <= 0) return hipSuccess;
-    dim3 grid((unsigned)((p.max_hist + NW * 32 - 1) / (NW * 32)), (unsigned)p.Hkv, (unsigned)p.batch);
-    hipLaunchKernelGGL((bwd_dkdv_kernel<D, NW>), grid, dim3(NW * 64), 0, s, p);
+    const int64_t n_kt = (p.max_hist + NW * 32 - 1) / (NW * 32);
+    const int64_t n_blocks = work_grid((int64_t)p.batch * p.Hkv, n_kt);
+    if (n_blocks >= (1ll << 31)) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((bwd_dkdv_kernel<D, NW>), dim3((unsigned)n_blocks), dim3(NW * 64), 0, s, p, (int)n_kt);
     return hipGetLastError();
 }
 

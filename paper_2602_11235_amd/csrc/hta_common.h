@@ -53,6 +53,29 @@ void timing_end(int kind, hipStream_t s);
 size_t schedule_bytes(int32_t batch);
 hipError_t launch_schedule(const Params& p, int32_t* order, hipStream_t s);
 __device__ inline int scheduled_user(const Params& p, int slot) { return p.order ? p.order[slot] : slot; }
+// Placement of workgroups.  Work is a list of groups (user slot, y) -- y = kv head (x head chunk) -- each with up
+// to `tpg` tiles that share operands (the K/V of the group, or its Q/dO).  The chip has 8 XCDs, each with its own
+// L2, and hands consecutive workgroup ids to them round-robin; so id -> (xcd = id % 8, slot = id / 8), a group lives
+// on one XCD (its tiles are consecutive slots there, so they also run close in time), and groups are dealt to the
+// XCDs round-robin in schedule order, which keeps the long-first order inside every XCD.  Only locality depends
+// on the round-robin assumption, never correctness.
+constexpr int N_XCD = 8;
+struct WorkItem {
+    int user_slot, y, tile;
+    bool valid;
+};
+__device__ inline WorkItem decode_work(unsigned id, int n_groups, int ny, int tpg) {
+    const int xcd = id % N_XCD, slot = id / N_XCD;
+    const int gl = slot / tpg;
+    const int group = gl * N_XCD + xcd;
+    WorkItem w;
+    w.valid = group < n_groups;
+    w.tile = slot - gl * tpg;
+    w.user_slot = group / ny;
+    w.y = group - w.user_slot * ny;
+    return w;
+}
+inline int64_t work_grid(int64_t n_groups, int64_t tpg) { return ((n_groups + N_XCD - 1) / N_XCD) * N_XCD * tpg; }
 // fill `n` 32-bit words with zero (a kernel, so that a caller may capture the call in a HIP graph)
 hipError_t launch_zero_words(void* ptr, size_t n_words, hipStream_t s);
 

@@ -34,7 +34,7 @@ struct Tile {
 };
 
 template <int D, int RB, int NW>
-__global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb, int n_hc) {
+__global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb, int n_hc, int tpg) {
     constexpr int NT = NW * 64;
     constexpr int KS = Tile<D>::KS, VS = Tile<D>::VS;
     constexpr int CPR = D / 8;                     // 16-byte chunks per K/V row
@@ -44,12 +44,14 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb,
     __shared__ __attribute__((aligned(16))) __bf16 smem[Tile<D>::LDS_ELEMS];
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
-    const int b = scheduled_user(p, blockIdx.z);
-    const int g = blockIdx.y / n_hc, hc = blockIdx.y % n_hc;
+    const WorkItem w = decode_work(blockIdx.x, p.batch * p.Hkv * n_hc, p.Hkv * n_hc, tpg);
+    if (!w.valid) return;
+    const int b = scheduled_user(p, w.user_slot);
+    const int g = w.y / n_hc, hc = w.y % n_hc;
     const int L = p.hist_len[b], T = p.n_targets[b];
     const int n_rows = p.layer == 0 ? L + T : T;
     const int BM = (NW / hpb) * RB * 32;
-    const int tile_row0 = blockIdx.x * BM;
+    const int tile_row0 = w.tile * BM;
     if (tile_row0 >= n_rows) return;  // uniform for the whole workgroup
     const int r = p.Hq / p.Hkv;
     const int h = g * r + hc * hpb + wave % hpb;
@@ -266,9 +268,9 @@ hipError_t launch(const Params& p, hipStream_t s) {
     const int64_t rows = max_query_rows(p);
     if (rows <= 0) return hipSuccess;
     const int64_t n_rt = (rows + BM - 1) / BM;
-    if ((int64_t)p.Hkv * n_hc > 65535) return hipErrorInvalidValue;
-    dim3 grid((unsigned)n_rt, (unsigned)(p.Hkv * n_hc), (unsigned)p.batch);
-    hipLaunchKernelGGL((fwd_bf16_kernel<D, RB, NW>), grid, dim3(NW * 64), 0, s, p, hpb, n_hc);
+    const int64_t n_blocks = work_grid((int64_t)p.batch * p.Hkv * n_hc, n_rt);
+    if (n_blocks >= (1ll << 31)) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((fwd_bf16_kernel<D, RB, NW>), dim3((unsigned)n_blocks), dim3(NW * 64), 0, s, p, hpb, n_hc, (int)n_rt);
     return hipGetLastError();
 }
 
