@@ -315,10 +315,14 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(Params p, int hpb, i
 }
 
 // ---------------------------------------------------------------------------------------- dK, dV
-constexpr int UPI = 2;  // (head, 32-row block) units staged and consumed per loop iteration of the dK/dV kernel
+// (head, 32-row block) units staged and consumed per loop iteration (= per workgroup barrier) of the dK/dV kernel:
+// as many as fit twice (double buffering) into about 75 KB of LDS, so that two workgroups share a CU
+template <int D>
+constexpr int units_per_iteration() { return D <= 64 ? 4 : 2; }
 
 template <int D, int NW>
 struct DkdvSmem {
+    static constexpr int UPI = units_per_iteration<D>();
     static constexpr int QS = D + 8;                    // Q/dO tile row pitch (elements)
     static constexpr int TILE = 32 * QS;                // one 32-row tile
     static constexpr size_t UNIT_BYTES = (size_t)2 * TILE * 2 + 2 * 32 * sizeof(float);  // Q, dO, lse2[32], delta[32]
@@ -330,7 +334,7 @@ struct DkdvSmem {
 template <int D, int NW>
 __global__ __launch_bounds__(NW * 64, 2) void bwd_dkdv_kernel(Params p, int tpg) {
     using SM = DkdvSmem<D, NW>;
-    constexpr int NT = NW * 64, QS = SM::QS;
+    constexpr int NT = NW * 64, QS = SM::QS, UPI = SM::UPI;
     constexpr int CPR = D / 8, NCH = UPI * 32 * CPR, CH = (NCH + NT - 1) / NT;
     constexpr int NKS = D / 16, NDB = D / 32;
     static_assert(NT >= UPI * 64, "one lane per lse/delta value");
