@@ -350,7 +350,7 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dkdv_kernel(Params p, int tpg)
     const int n_rows = p.layer == 0 ? L + T : T;
     const int r = p.Hq / p.Hkv;
     const int64_t q_base = p.q_off[b], kv_base = p.kv_off[b];
-    const float c2 = p.scale * LOG2E;
+    const float c2 = p.scale * LOG2E, inv_scale = 1.f / p.scale;
     const int dhalf16 = 16 * ((lane >> 4) & 1);
     const int kw = key0 + wave * 32;        // first key of this wave
     const bool wave_live = kw < L;          // a wave past the history only helps staging
@@ -381,7 +381,9 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dkdv_kernel(Params p, int tpg)
     const int n_units = n_rb * r;  // unit u = (32-row block u / r, head g*r + u % r)
     const int n_iter = (n_units + UPI - 1) / UPI;
     uint4 qreg[CH], doreg[CH];
-    float sreg = 0.f;  // threads 0..64*UPI-1: lse2 (first 32 of each 64) or delta (last 32) of one row of one unit
+    // threads 0..64*UPI-1: -lse/scale (first 32 of each 64) or -delta (last 32) of one row of one unit: the values
+    // the S and dP accumulators start from, so that the products come out as S - lse/scale and dP - delta
+    float sreg = 0.f;
     auto load_units = [&](int it) {
         static_for<0, CH>([&](auto I) {
             constexpr int i = decltype(I)::value;
@@ -405,8 +407,8 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dkdv_kernel(Params p, int tpg)
             const int row = (u / r) * 32 + (tid & 31);
             const bool live = row < n_rows;
             const int64_t idx = (int64_t)(g * r + u % r) * p.total_q + q_base + (live ? row : n_rows - 1);
-            // rows past the end get lse = +inf, i.e. P = 0
-            sreg = (tid & 32) == 0 ? (live ? p.lse[idx] * LOG2E : INFINITY) : p.delta[idx];
+            // rows past the end start from -inf, i.e. P = 0
+            sreg = (tid & 32) == 0 ? (live ? -p.lse[idx] * inv_scale : -INFINITY) : -p.delta[idx];
         }
     };
     auto store_units = [&](int buf) {
@@ -436,23 +438,23 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dkdv_kernel(Params p, int tpg)
             qa[ks] = *(const bf16x8*)(Qs + l32 * QS + ks * 16 + 8 * hf);
             da[ks] = *(const bf16x8*)(dOs + l32 * QS + ks * 16 + 8 * hf);
         }
-        floatx4 l4[4], d4[4];  // registers 4j..4j+3 hold rows 8j+4hf .. 8j+4hf+3
+        // accumulators start from -lse/scale and -delta of their rows (registers 4j..4j+3 hold rows 8j+4hf .. +3)
+        floatx4 l4[4], d4[4];
 #pragma unroll
         for (int j = 0; j < 4; j++) {
             l4[j] = *(const floatx4*)(ss + 8 * j + 4 * hf);
             d4[j] = *(const floatx4*)(ss + 32 + 8 * j + 4 * hf);
         }
-        floatx16 S, dP;  // [row (registers)][key (lanes)]
+        floatx16 S = __builtin_shufflevector(__builtin_shufflevector(l4[0], l4[1], 0, 1, 2, 3, 4, 5, 6, 7),
+                                             __builtin_shufflevector(l4[2], l4[3], 0, 1, 2, 3, 4, 5, 6, 7), 0, 1, 2, 3, 4,
+                                             5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
+        floatx16 dP = __builtin_shufflevector(__builtin_shufflevector(d4[0], d4[1], 0, 1, 2, 3, 4, 5, 6, 7),
+                                              __builtin_shufflevector(d4[2], d4[3], 0, 1, 2, 3, 4, 5, 6, 7), 0, 1, 2, 3, 4,
+                                              5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);  // [row (registers)][key (lanes)]
 #pragma unroll
         for (int ks = 0; ks < NKS; ks++) {
-            if (ks == 0) {
-                const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-                S = mfma32(qa[ks], kf[ks], zero);
-                dP = mfma32(da[ks], vf[ks], zero);
-            } else {
-                S = mfma32(qa[ks], kf[ks], S);
-                dP = mfma32(da[ks], vf[ks], dP);
-            }
+            S = mfma32(qa[ks], kf[ks], S);     // S - lse/scale
+            dP = mfma32(da[ks], vf[ks], dP);   // dP - delta
         }
         bf16x8 dot[NDB][2], qt[NDB][2];
 #pragma unroll
@@ -468,10 +470,10 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dkdv_kernel(Params p, int tpg)
 #pragma unroll
             for (int e = 0; e < 4; e++) {
                 const int v = 4 * j + e;
-                float pw = fast_exp2(fmaf(S[v], c2, -l4[j][e]));
+                float pw = fast_exp2(S[v] * c2);
                 if (decltype(ragged)::value) pw = key_live ? pw : 0.f;  // keys past the history carry no weight
                 pb[v / 8][v % 8] = (__bf16)pw;
-                dsb[v / 8][v % 8] = (__bf16)(pw * (dP[v] - d4[j][e]));
+                dsb[v / 8][v % 8] = (__bf16)(pw * dP[v]);
             }
         }
         // dV[key][d] += P^T[key][row] dO[row][d];  dK[key][d] += dS^T[key][row] Q[row][d]

@@ -283,8 +283,11 @@ bool bf16_supported(int32_t d, int32_t Hq, int32_t Hkv) {
 }
 
 hipError_t launch_fwd_bf16(const Params& p, hipStream_t s) {
+    // Eight waves of one 32-row block each whenever the head group fills them (r a multiple of 4): the small
+    // register footprint lets four waves share a SIMD, which hides more latency than a second row block per
+    // wave saves in LDS reads.  Otherwise four waves with two row blocks each.
     const int r = p.Hq / p.Hkv;
-    const bool wide = (r % 8) == 0;
+    const bool wide = (r % 4) == 0;
     hipError_t e;
     timing_begin(MTFM_HTA_KERNEL_FWD, s);
     switch (p.d) {
