@@ -332,7 +332,7 @@ struct DkdvSmem {
 
 // one workgroup per (user, kv head, tile of NW*32 history keys)
 template <int D, int NW>
-__global__ __launch_bounds__(NW * 64, 2) void bwd_dkdv_kernel(Params p, int tpg) {
+__global__ __launch_bounds__(NW * 64, D > 64 ? 1 : 2) void bwd_dkdv_kernel(Params p, int tpg) {
     using SM = DkdvSmem<D, NW>;
     constexpr int NT = NW * 64, QS = SM::QS, UPI = SM::UPI;
     constexpr int CPR = D / 8, NCH = UPI * 32 * CPR, CH = (NCH + NT - 1) / NT;
