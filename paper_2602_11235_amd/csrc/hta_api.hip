@@ -22,19 +22,21 @@ int fail(int code, const char* fmt, ...) {
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Workspace {
-    size_t order_off, delta_off, total;
+    size_t order_off, delta_off, lse_off, total;
 };
 
 // Layout of the caller's workspace (bf16 path; the fp32 debug path needs none):
 //   order [batch] int32   users by decreasing tile count, rebuilt by every call
-//   delta [Hq][total_q] f32   backward only
+//   -delta and -lse/scale, [Hq][total_q] f32 each   backward only
 Workspace plan_workspace(int dtype, int is_bwd, int32_t batch, int64_t total_q, int32_t Hq) {
-    Workspace w{0, 0, 0};
+    Workspace w{0, 0, 0, 0};
     if (dtype == MTFM_HTA_FP32) return w;
     w.order_off = 0;
     w.total = hta::schedule_bytes(batch);
     if (is_bwd) {
         w.delta_off = w.total;
+        w.total += align256((size_t)total_q * Hq * sizeof(float));
+        w.lse_off = w.total;
         w.total += align256((size_t)total_q * Hq * sizeof(float));
     }
     return w;
@@ -178,7 +180,8 @@ int mtfm_hta_bwd(const void* dout, const void* q, const void* k, const void* v, 
     p.Hq = Hq; p.Hkv = Hkv; p.d = head_dim; p.scale = softmax_scale; p.layer = layer;
     if (w.total > 0) {
         char* base = (char*)workspace;
-        p.delta = (float*)(base + w.delta_off);
+        p.neg_delta = (float*)(base + w.delta_off);
+        p.neg_lse_s = (float*)(base + w.lse_off);
     }
     hipStream_t s = (hipStream_t)stream;
     hipError_t e = hipSuccess;

@@ -83,7 +83,11 @@ __global__ __launch_bounds__(256) void bwd_pre_kernel(Params p) {
             part = fmaf(dof[j], (float)ov[j], part);
         }
         const float delta = group_sum(part, LPR);
-        if (sub == 0) p.delta[(int64_t)h * p.total_q + q_row] = delta;
+        const float lse = p.lse[(int64_t)h * p.total_q + q_row];
+        if (sub == 0) {
+            p.neg_delta[(int64_t)h * p.total_q + q_row] = -delta;
+            p.neg_lse_s[(int64_t)h * p.total_q + q_row] = -lse / p.scale;
+        }
         if (is_target) {
             const bf16x8 qv = *(const bf16x8*)(qg + off);
             float qf[8], sp = 0.f, dpp = 0.f;
@@ -95,7 +99,7 @@ __global__ __launch_bounds__(256) void bwd_pre_kernel(Params p) {
             }
             const float s = group_sum(sp, LPR) * p.scale;
             const float dp = group_sum(dpp, LPR);
-            const float pw = __expf(s - p.lse[(int64_t)h * p.total_q + q_row]);
+            const float pw = __expf(s - lse);
             const float ds = pw * (dp - delta) * p.scale;
 #pragma unroll
             for (int j = 0; j < 8; j++) {
@@ -162,7 +166,7 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(Params p, int hpb, i
             dof[rb][ks] = *(const bf16x8*)((const __bf16*)p.dout + off + ks * 16);
         }
         lse2[rb] = p.lse[(int64_t)h * p.total_q + q_base + row] * LOG2E;
-        dl[rb] = p.delta[(int64_t)h * p.total_q + q_base + row];
+        dl[rb] = p.neg_delta[(int64_t)h * p.total_q + q_base + row];  // -delta
     }
     floatx16 dQ[RB][NDB];  // dQ^T: [d (registers)][row (lanes)]
 #pragma unroll
@@ -233,7 +237,7 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(Params p, int hpb, i
 #pragma unroll
             for (int v = 0; v < 16; v++) {
                 const float pw = fast_exp2(fmaf(S[rb][v], c2, -lse2[rb]));
-                dsb[rb][v / 8][v % 8] = (__bf16)(pw * (dP[rb][v] - dl[rb]));
+                dsb[rb][v / 8][v % 8] = (__bf16)(pw * (dP[rb][v] + dl[rb]));
             }
         // dQ^T[d][row] += sum_key K[key][d] dS^T[key][row]
 #pragma unroll
@@ -289,7 +293,7 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(Params p, int hpb, i
             sp += other_half(sp);
             dpp += other_half(dpp);
             const float pw = fast_exp2(fmaf(sp, c2, -lse2[rb]));
-            const float ds = pw * (dpp - dl[rb]);
+            const float ds = pw * (dpp + dl[rb]);
 #pragma unroll
             for (int db = 0; db < NDB; db++)
 #pragma unroll
@@ -315,30 +319,42 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(Params p, int hpb, i
 }
 
 // ---------------------------------------------------------------------------------------- dK, dV
-// (head, 32-row block) units staged and consumed per loop iteration (= per workgroup barrier) of the dK/dV kernel:
-// as many as fit twice (double buffering) into about 75 KB of LDS, so that two workgroups share a CU
-template <int D>
-constexpr int units_per_iteration() { return D <= 64 ? 4 : 2; }
-
 template <int D, int NW>
 struct DkdvSmem {
-    static constexpr int UPI = units_per_iteration<D>();
-    static constexpr int QS = D + 8;                    // Q/dO tile row pitch (elements)
-    static constexpr int TILE = 32 * QS;                // one 32-row tile
-    static constexpr size_t UNIT_BYTES = (size_t)2 * TILE * 2 + 2 * 32 * sizeof(float);  // Q, dO, lse2[32], delta[32]
-    static constexpr size_t BUF_BYTES = UPI * UNIT_BYTES;
-    static constexpr size_t BYTES = 2 * BUF_BYTES;      // double buffered
+    static constexpr int UPI = 2;      // (head, 32-row block) units per loop iteration, i.e. per workgroup barrier
+    static constexpr int NSTAGE = 3;   // iterations resident in LDS: one being consumed, two in flight
+    static constexpr int TILE = 32 * D;                 // one unpadded, swizzled 32-row tile (elements)
+    static constexpr size_t UNIT_BYTES = (size_t)2 * TILE * 2 + 2 * 32 * sizeof(float);  // Q, dO, -lse/scale[32], -delta[32]
+    static constexpr size_t STAGE_BYTES = UPI * UNIT_BYTES;
+    static constexpr size_t BYTES = NSTAGE * STAGE_BYTES;
 };
 
-// one workgroup per (user, kv head, tile of NW*32 history keys)
+// One workgroup per (user, kv head, tile of NW*32 history keys).  Q and dO tiles travel global -> LDS directly
+// (no register stop-over), two iterations ahead of their use.
 template <int D, int NW>
 __global__ __launch_bounds__(NW * 64, D > 64 ? 1 : 2) void bwd_dkdv_kernel(Params p, int tpg) {
     using SM = DkdvSmem<D, NW>;
-    constexpr int NT = NW * 64, QS = SM::QS, UPI = SM::UPI;
-    constexpr int CPR = D / 8, NCH = UPI * 32 * CPR, CH = (NCH + NT - 1) / NT;
+    constexpr int UPI = SM::UPI, NSTAGE = SM::NSTAGE;
     constexpr int NKS = D / 16, NDB = D / 32;
-    static_assert(NT >= UPI * 64, "one lane per lse/delta value");
-    __shared__ __attribute__((aligned(16))) unsigned char smem_raw[SM::BYTES];
+    constexpr int CPR = D / 8;                  // 16-byte chunks per row
+    constexpr int RPI = 64 / CPR;               // rows covered by one wave-wide 1 KB copy
+    constexpr int IPT = 32 / RPI;               // copies per tile
+    constexpr int IPW = (IPT + NW - 1) / NW;    // copies per tile issued by one wave (the last may be idle)
+    constexpr int COPIES = UPI * 2 * IPW;       // direct copies per wave and iteration (when the wave takes part)
+    static_assert(IPT % NW == 0 || IPT < NW, "tile copies must split evenly over the waves");
+    static_assert(UPI <= NW, "wave uu copies the row statistics of unit uu");
+    // One array per stage: copies in flight into one stage and reads from another are then provably disjoint, so the
+    // compiler need not drain the copies before every LDS read.
+    __shared__ __attribute__((aligned(1024))) unsigned char stage0[SM::STAGE_BYTES];
+    __shared__ __attribute__((aligned(1024))) unsigned char stage1[SM::STAGE_BYTES];
+    __shared__ __attribute__((aligned(1024))) unsigned char stage2[SM::STAGE_BYTES];
+    static_assert(NSTAGE == 3, "three stage arrays");
+    auto stage_ptr = [&](auto St) -> unsigned char* {
+        constexpr int st = decltype(St)::value % 3;
+        if constexpr (st == 0) return stage0;
+        if constexpr (st == 1) return stage1;
+        return stage2;
+    };
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
     const WorkItem w = decode_work(blockIdx.x, p.batch * p.Hkv, p.Hkv, tpg);
@@ -350,12 +366,29 @@ __global__ __launch_bounds__(NW * 64, D > 64 ? 1 : 2) void bwd_dkdv_kernel(Param
     const int n_rows = p.layer == 0 ? L + T : T;
     const int r = p.Hq / p.Hkv;
     const int64_t q_base = p.q_off[b], kv_base = p.kv_off[b];
-    const float c2 = p.scale * LOG2E, inv_scale = 1.f / p.scale;
-    const int dhalf16 = 16 * ((lane >> 4) & 1);
+    const float c2 = p.scale * LOG2E;
     const int kw = key0 + wave * 32;        // first key of this wave
     const bool wave_live = kw < L;          // a wave past the history only helps staging
     const bool key_live = kw + l32 < L;
     const bool wave_ragged = kw + 32 > L;
+    const bool copies = IPT >= NW || wave < IPT;   // does this wave issue tile copies?
+
+    // per-lane element offsets into a swizzled tile
+    int nat_off[NKS];   // row l32, chunk 2*ks + hf: fragments with the row on the lane
+#pragma unroll
+    for (int ks = 0; ks < NKS; ks++) nat_off[ks] = l32 * D + (((2 * ks + hf) ^ swizzle<D>(l32)) << 3);
+    // transposed fragments: rows 4*hf + (lane%16)/4 and 8 below (+16 per k-step, which leaves the swizzle
+    // unchanged), 4 elements at column 32*db + 16*((lane/16)%2) + 4*(lane%4)
+    int tr_lo[NDB], tr_hi[NDB];
+    {
+        const int pl = lane & 15, trow = 4 * hf + (pl >> 2);
+#pragma unroll
+        for (int db = 0; db < NDB; db++) {
+            const int chunk = 4 * db + 2 * ((lane >> 4) & 1) + ((pl & 3) >> 1);
+            tr_lo[db] = trow * D + ((chunk ^ swizzle<D>(trow)) << 3) + 4 * (pl & 1);
+            tr_hi[db] = (trow + 8) * D + ((chunk ^ swizzle<D>(trow + 8)) << 3) + 4 * (pl & 1);
+        }
+    }
 
     // stationary operands: K and V rows of the wave's keys (B operand of S = Q K^T and dP = dO V^T)
     bf16x8 kf[NKS], vf[NKS];
@@ -376,67 +409,65 @@ __global__ __launch_bounds__(NW * 64, D > 64 ? 1 : 2) void bwd_dkdv_kernel(Param
             dK[db][v] = 0.f;
             dV[db][v] = 0.f;
         }
+    // From here on the only vector-memory traffic of the loop are the asynchronous copies, which this code counts
+    // itself; the compiler must not be left with pending loads of its own that it would wait for inside the loop.
+    wait_vmem_loads();
 
     const int n_rb = (n_rows + 31) / 32;
     const int n_units = n_rb * r;  // unit u = (32-row block u / r, head g*r + u % r)
     const int n_iter = (n_units + UPI - 1) / UPI;
-    uint4 qreg[CH], doreg[CH];
-    // threads 0..64*UPI-1: -lse/scale (first 32 of each 64) or -delta (last 32) of one row of one unit: the values
-    // the S and dP accumulators start from, so that the products come out as S - lse/scale and dP - delta
-    float sreg = 0.f;
-    auto load_units = [&](int it) {
-        static_for<0, CH>([&](auto I) {
-            constexpr int i = decltype(I)::value;
-            const int c = tid + i * NT;
-            qreg[i] = make_uint4(0, 0, 0, 0);
-            doreg[i] = make_uint4(0, 0, 0, 0);
-            if (c < NCH) {
-                int u = it * UPI + c / (32 * CPR);
-                u = u < n_units ? u : n_units - 1;  // a missing unit repeats the last one and is not consumed
-                const int cc = c % (32 * CPR);
-                int row = (u / r) * 32 + cc / CPR;
-                row = row < n_rows ? row : n_rows - 1;
-                const int64_t off = ((q_base + row) * p.Hq + g * r + u % r) * D + (cc % CPR) * 8;
-                qreg[i] = *(const uint4*)((const __bf16*)p.q + off);
-                doreg[i] = *(const uint4*)((const __bf16*)p.dout + off);
+
+    // Q and dO tiles of iteration `it` -> stage it % NSTAGE.  Copy j of a tile covers rows j*RPI .. j*RPI+RPI-1:
+    // lane i lands at chunk position i % CPR of row j*RPI + i / CPR, so it fetches the chunk that belongs there.
+    auto issue_tiles = [&](int it, auto St) {
+        unsigned char* stage = stage_ptr(St);
+#pragma unroll
+        for (int uu = 0; uu < UPI; uu++) {
+            int u = it * UPI + uu;
+            u = u < n_units ? u : n_units - 1;  // a missing unit repeats the last one and is not consumed
+            const int row0 = (u / r) * 32, h = g * r + u % r;
+#pragma unroll
+            for (int jj = 0; jj < (copies ? IPW : 0); jj++) {
+                const int j = wave + jj * NW;   // < IPT by construction
+                const int trow = j * RPI + lane / CPR;
+                int row = row0 + trow;
+                row = row < n_rows ? row : n_rows - 1;  // rows past the end repeat the last row; their P is forced to 0
+                const int chunk = (lane % CPR) ^ swizzle<D>(trow);
+                const int64_t off = ((q_base + row) * p.Hq + h) * D + chunk * 8;
+                unsigned char* dst = stage + uu * SM::UNIT_BYTES + (size_t)j * 1024;
+                copy16_global_to_lds((const __bf16*)p.q + off, dst);
+                copy16_global_to_lds((const __bf16*)p.dout + off, dst + (size_t)SM::TILE * 2);
             }
-        });
-        if (tid < 64 * UPI) {
-            int u = it * UPI + tid / 64;
-            u = u < n_units ? u : n_units - 1;
-            const int row = (u / r) * 32 + (tid & 31);
-            const bool live = row < n_rows;
-            const int64_t idx = (int64_t)(g * r + u % r) * p.total_q + q_base + (live ? row : n_rows - 1);
-            // rows past the end start from -inf, i.e. P = 0
-            sreg = (tid & 32) == 0 ? (live ? -p.lse[idx] * inv_scale : -INFINITY) : -p.delta[idx];
+            // row statistics of the unit, copied by wave uu: lanes 0..31 fetch -lse/scale, lanes 32..63 -delta of row
+            // lane % 32.  These are the values the S and dP accumulators start from, so that the products come out
+            // as S - lse/scale and dP - delta.  (Rows past the end repeat the last row and are masked in the unit.)
+            if (wave == uu) {
+                int row = row0 + l32;
+                row = row < n_rows ? row : n_rows - 1;
+                const float* src = (hf == 0 ? p.neg_lse_s : p.neg_delta) + (int64_t)h * p.total_q + q_base + row;
+                copy4_global_to_lds(src, stage + uu * SM::UNIT_BYTES + (size_t)4 * SM::TILE);
+            }
         }
     };
-    auto store_units = [&](int buf) {
-        unsigned char* base = smem_raw + buf * SM::BUF_BYTES;
-        static_for<0, CH>([&](auto I) {
-            constexpr int i = decltype(I)::value;
-            const int c = tid + i * NT;
-            if (c < NCH) {
-                const int cc = c % (32 * CPR);
-                __bf16* Qd = (__bf16*)(base + (c / (32 * CPR)) * SM::UNIT_BYTES);
-                *(uint4*)(Qd + (cc / CPR) * QS + (cc % CPR) * 8) = qreg[i];
-                *(uint4*)(Qd + SM::TILE + (cc / CPR) * QS + (cc % CPR) * 8) = doreg[i];
-            }
-        });
-        if (tid < 64 * UPI) ((float*)(base + (tid / 64) * SM::UNIT_BYTES + (size_t)4 * SM::TILE))[tid & 63] = sreg;
+    // copies a wave has issued for one iteration
+    auto wait_previous_iteration = [&]() {
+        if (copies) {
+            if (wave < UPI) wait_vmem_outstanding<COPIES + 1>(); else wait_vmem_outstanding<COPIES>();
+        } else {
+            if (wave < UPI) wait_vmem_outstanding<1>(); else wait_vmem_outstanding<0>();
+        }
     };
     // one (head, 32-row block) unit against the wave's 32 keys
-    auto unit = [&](const unsigned char* ubase, auto ragged) {
+    auto unit = [&](const unsigned char* ubase, auto ragged, int rows_live) {
         const __bf16* Qs = (const __bf16*)ubase;
         const __bf16* dOs = Qs + SM::TILE;
         const float* ss = (const float*)(dOs + SM::TILE);
-        // all LDS operands are requested up front, in the order they are consumed: their latency then hides
-        // behind the MFMAs and the exponentials instead of stalling each product
+        // all LDS operands are requested up front, in the order they are consumed
         bf16x8 qa[NKS], da[NKS];
 #pragma unroll
         for (int ks = 0; ks < NKS; ks++) {
-            qa[ks] = *(const bf16x8*)(Qs + l32 * QS + ks * 16 + 8 * hf);
-            da[ks] = *(const bf16x8*)(dOs + l32 * QS + ks * 16 + 8 * hf);
+            qa[ks] = *(const bf16x8*)(Qs + nat_off[ks]);
+            da[ks] = *(const bf16x8*)(dOs + nat_off[ks]);
         }
         // accumulators start from -lse/scale and -delta of their rows (registers 4j..4j+3 hold rows 8j+4hf .. +3)
         floatx4 l4[4], d4[4];
@@ -461,20 +492,17 @@ __global__ __launch_bounds__(NW * 64, D > 64 ? 1 : 2) void bwd_dkdv_kernel(Param
         for (int db = 0; db < NDB; db++)
 #pragma unroll
             for (int s2 = 0; s2 < 2; s2++) {
-                dot[db][s2] = lds_read_tr_8(dOs, QS, 16 * s2 + 4 * hf, db * 32 + dhalf16, lane);
-                qt[db][s2] = lds_read_tr_8(Qs, QS, 16 * s2 + 4 * hf, db * 32 + dhalf16, lane);
+                dot[db][s2] = lds_read_tr_pair(dOs + tr_lo[db] + 16 * s2 * D, dOs + tr_hi[db] + 16 * s2 * D);
+                qt[db][s2] = lds_read_tr_pair(Qs + tr_lo[db] + 16 * s2 * D, Qs + tr_hi[db] + 16 * s2 * D);
             }
         bf16x8 pb[2], dsb[2];
 #pragma unroll
-        for (int j = 0; j < 4; j++) {
-#pragma unroll
-            for (int e = 0; e < 4; e++) {
-                const int v = 4 * j + e;
-                float pw = fast_exp2(S[v] * c2);
-                if (decltype(ragged)::value) pw = key_live ? pw : 0.f;  // keys past the history carry no weight
-                pb[v / 8][v % 8] = (__bf16)pw;
-                dsb[v / 8][v % 8] = (__bf16)(pw * dP[v]);
-            }
+        for (int v = 0; v < 16; v++) {
+            float pw = fast_exp2(S[v] * c2);
+            // keys past the history and rows past the end of the user carry no weight
+            if (decltype(ragged)::value) pw = (key_live && 8 * (v / 4) + 4 * hf + (v % 4) < rows_live) ? pw : 0.f;
+            pb[v / 8][v % 8] = (__bf16)pw;
+            dsb[v / 8][v % 8] = (__bf16)(pw * dP[v]);
         }
         // dV[key][d] += P^T[key][row] dO[row][d];  dK[key][d] += dS^T[key][row] Q[row][d]
 #pragma unroll
@@ -486,28 +514,48 @@ __global__ __launch_bounds__(NW * 64, D > 64 ? 1 : 2) void bwd_dkdv_kernel(Param
             }
     };
 
+    const std::integral_constant<int, 0> st0{};
+    const std::integral_constant<int, 1> st1{};
+    const std::integral_constant<int, 2> st2{};
+    // prologue: iteration 0 complete in LDS, iteration 1 in flight
     if (n_iter > 0) {
-        load_units(0);
-        store_units(0);
+        issue_tiles(0, st0);
+        if (n_iter > 1) {
+            issue_tiles(1, st1);
+            wait_previous_iteration();
+        } else {
+            wait_vmem_outstanding<0>();
+        }
     }
-    __syncthreads();
-    wait_vmem_loads();
-    for (int it = 0; it < n_iter; it++) {
-        const unsigned char* base = smem_raw + (it & 1) * SM::BUF_BYTES;
-        if (it + 1 < n_iter) load_units(it + 1);
+    lds_barrier();
+    // iteration `it` consumes stage St = it % 3 and refills stage (it+2) % 3
+    auto iteration = [&](int it, auto St) {
+        constexpr int st = decltype(St)::value;
+        const unsigned char* base = stage_ptr(St);
+        const bool more2 = it + 2 < n_iter;
+        // stage (it+2)%3 was last read in iteration it-1, which every wave has left
+        if (more2) issue_tiles(it + 2, std::integral_constant<int, (st + 2) % 3>{});
         if (wave_live) {
 #pragma unroll
             for (int uu = 0; uu < UPI; uu++) {
-                if (it * UPI + uu < n_units) {
-                    if (wave_ragged)
-                        unit(base + uu * SM::UNIT_BYTES, std::true_type{});
+                const int u = it * UPI + uu;
+                if (u < n_units) {
+                    const int rows_live = n_rows - (u / r) * 32;
+                    if (wave_ragged || rows_live < 32)
+                        unit(base + uu * SM::UNIT_BYTES, std::true_type{}, rows_live);
                     else
-                        unit(base + uu * SM::UNIT_BYTES, std::false_type{});
+                        unit(base + uu * SM::UNIT_BYTES, std::false_type{}, 32);
                 }
             }
         }
-        if (it + 1 < n_iter) store_units((it + 1) & 1);
-        __syncthreads();
+        // the copies of iteration it+1 (issued one iteration ago) must have landed; those of it+2 may stay in flight
+        if (more2) wait_previous_iteration(); else wait_vmem_outstanding<0>();
+        lds_barrier();
+    };
+    for (int it = 0; it < n_iter; it += 3) {
+        iteration(it, st0);
+        if (it + 1 < n_iter) iteration(it + 1, st1);
+        if (it + 2 < n_iter) iteration(it + 2, st2);
     }
 
     // write the wave's 32 key rows: lanes cover 32 consecutive d

@@ -31,7 +31,8 @@ struct Params {
     float scale;
     int32_t layer;        // 0 full (queries = all tokens), 1 target (queries = target tokens)
     // carved out of the caller's workspace (bwd)
-    float* delta;         // [Hq][total_q]   <dout_i, out_i>
+    float* neg_delta;     // [Hq][total_q]   -<dout_i, out_i>
+    float* neg_lse_s;     // [Hq][total_q]   -lse_i / scale: what the S accumulators of the dK/dV pass start from
     const int32_t* order; // [batch] users by decreasing tile count (bf16 path), or null = identity
 };
 

@@ -86,4 +86,53 @@ __device__ inline bf16x8 lds_read_tr_8(const __bf16* tile, int stride, int row0,
     return __builtin_bit_cast(bf16x8, r);
 }
 
+// The two 8-byte transposed reads of lds_read_tr_8 at precomputed per-lane addresses (rows r..r+3 and r+8..r+11).
+__device__ inline bf16x8 lds_read_tr_pair(const __bf16* a0, const __bf16* a1) {
+    short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((HTA_LDS short4v*)(HTA_LDS char*)a0);
+    short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((HTA_LDS short4v*)(HTA_LDS char*)a1);
+    typedef short short8v __attribute__((ext_vector_type(8)));
+    short8v r = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, r);
+}
+
+// Unpadded LDS tiles (row pitch = D elements) with an XOR swizzle of their 16-byte chunks: the chunk that holds
+// elements 8c .. 8c+7 of row `row` sits at chunk position c ^ swizzle<D>(row).  Chosen so that both access
+// patterns of the kernels are free of bank conflicts: 16 lanes reading the same chunk of 16 consecutive rows,
+// and 32 lanes reading four consecutive chunks of four consecutive rows (the transposed read).
+template <int D>
+__device__ inline int swizzle(int row) {
+    if (D == 32) return (row >> 2) & 3;
+    if (D == 64) return (((row >> 1) & 1) << 2) | ((row >> 2) & 3);
+    return ((row & 3) << 2) | ((row >> 2) & 3);
+}
+
+// Asynchronous 16-byte copy global -> LDS without a register stop-over: lane i of the wave writes
+// lds_wave_base[16 i .. 16 i + 15] with the 16 bytes at its own global address (lds_wave_base must be the same
+// for all lanes).  Completion is tracked by the wave's vector-memory counter like any load, and is the caller's
+// business (wait_vmem_outstanding): the copy is issued from inline assembly precisely so that the compiler does
+// not drain it before every later LDS read.  Its own vmcnt waits for ordinary loads ignore these copies, which
+// only makes them wait longer than needed, never less (the counter retires in issue order).
+__device__ inline void copy16_global_to_lds(const void* global_lane_ptr, void* lds_wave_base) {
+    const uint32_t base =
+        __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)lds_wave_base);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(base), "v"(global_lane_ptr) : "memory");
+}
+
+// Same for 4 bytes per lane: lane i writes lds_wave_base[4 i .. 4 i + 3].
+__device__ inline void copy4_global_to_lds(const void* global_lane_ptr, void* lds_wave_base) {
+    const uint32_t base =
+        __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)lds_wave_base);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" : : "s"(base), "v"(global_lane_ptr) : "memory");
+}
+
+// wait until at most N vector-memory operations of this wave are still outstanding (N < 64)
+template <int N>
+__device__ inline void wait_vmem_outstanding() {
+    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | 0x0F70);
+}
+
+// all LDS traffic of this wave has completed, then wait for the other waves of the workgroup: orders LDS stores
+// and loads across the workgroup without also waiting for global loads that are still in flight
+__device__ inline void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 }  // namespace hta
