@@ -27,7 +27,7 @@ struct Workspace {
 
 // Layout of the caller's workspace (bf16 path; the fp32 debug path needs none):
 //   order [batch] int32   users by decreasing tile count, rebuilt by every call
-//   -delta and -lse/scale, [Hq][total_q] f32 each   backward only
+//   -delta and -lse/scale, [Hq][total_q] f32 each, the latter followed by one sentinel element   backward only
 Workspace plan_workspace(int dtype, int is_bwd, int32_t batch, int64_t total_q, int32_t Hq) {
     Workspace w{0, 0, 0, 0};
     if (dtype == MTFM_HTA_FP32) return w;
@@ -37,7 +37,7 @@ Workspace plan_workspace(int dtype, int is_bwd, int32_t batch, int64_t total_q, 
         w.delta_off = w.total;
         w.total += align256((size_t)total_q * Hq * sizeof(float));
         w.lse_off = w.total;
-        w.total += align256((size_t)total_q * Hq * sizeof(float));
+        w.total += align256(((size_t)total_q * Hq + 1) * sizeof(float));
     }
     return w;
 }

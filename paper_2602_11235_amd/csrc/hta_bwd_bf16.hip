@@ -50,6 +50,8 @@ __global__ __launch_bounds__(256) void bwd_pre_kernel(Params p) {
     const int item = blockIdx.x * IPB + threadIdx.x / LPR;  // (row, g) flattened, g fastest
     const int sub = threadIdx.x % LPR;
     const int row = item / p.Hkv, g = item % p.Hkv;
+    // behind the -lse/scale array: what the S accumulators of rows that do not exist start from in the dK/dV pass
+    if (blockIdx.x == 0 && blockIdx.z == 0 && threadIdx.x == 0) p.neg_lse_s[(int64_t)p.Hq * p.total_q] = -1e30f;
     if (row >= n_rows) return;  // whole lane groups leave together; group_sum only talks inside a group
     const int64_t q_row = (int64_t)p.q_off[b] + row;
     const int tok = (p.layer == 0 ? 0 : L) + row;
@@ -415,7 +417,7 @@ __global__ __launch_bounds__(NW * 64, D > 64 ? 1 : 2) void bwd_dkdv_kernel(Param
 
     const int n_rb = (n_rows + 31) / 32;
     const int n_units = n_rb * r;  // unit u = (32-row block u / r, head g*r + u % r)
-    const int n_iter = (n_units + UPI - 1) / UPI;
+    const int n_iter = (n_units + UPI - 1) / UPI;  // 0 for a user without query rows: dK = dV = 0 is still written
 
     // Q and dO tiles of iteration `it` -> stage it % NSTAGE.  Copy j of a tile covers rows j*RPI .. j*RPI+RPI-1:
     // lane i lands at chunk position i % CPR of row j*RPI + i / CPR, so it fetches the chunk that belongs there.
@@ -423,51 +425,66 @@ __global__ __launch_bounds__(NW * 64, D > 64 ? 1 : 2) void bwd_dkdv_kernel(Param
         unsigned char* stage = stage_ptr(St);
 #pragma unroll
         for (int uu = 0; uu < UPI; uu++) {
-            int u = it * UPI + uu;
-            u = u < n_units ? u : n_units - 1;  // a missing unit repeats the last one and is not consumed
+            const int u_true = it * UPI + uu;
+            const int u = u_true < n_units ? u_true : n_units - 1;  // a missing unit repeats the last one, with no weight
             const int row0 = (u / r) * 32, h = g * r + u % r;
 #pragma unroll
             for (int jj = 0; jj < (copies ? IPW : 0); jj++) {
                 const int j = wave + jj * NW;   // < IPT by construction
                 const int trow = j * RPI + lane / CPR;
                 int row = row0 + trow;
-                row = row < n_rows ? row : n_rows - 1;  // rows past the end repeat the last row; their P is forced to 0
+                row = row < n_rows ? row : n_rows - 1;  // rows past the end repeat the last row, with no weight
                 const int chunk = (lane % CPR) ^ swizzle<D>(trow);
                 const int64_t off = ((q_base + row) * p.Hq + h) * D + chunk * 8;
                 unsigned char* dst = stage + uu * SM::UNIT_BYTES + (size_t)j * 1024;
                 copy16_global_to_lds((const __bf16*)p.q + off, dst);
                 copy16_global_to_lds((const __bf16*)p.dout + off, dst + (size_t)SM::TILE * 2);
             }
-            // row statistics of the unit, copied by wave uu: lanes 0..31 fetch -lse/scale, lanes 32..63 -delta of row
+            // Row statistics of the unit, copied by wave uu: lanes 0..31 fetch -lse/scale, lanes 32..63 -delta of row
             // lane % 32.  These are the values the S and dP accumulators start from, so that the products come out
-            // as S - lse/scale and dP - delta.  (Rows past the end repeat the last row and are masked in the unit.)
+            // as S - lse/scale and dP - delta.  A row that does not exist (past the end of the user, or a whole unit
+            // past the last one) starts from the sentinel behind the -lse/scale array instead, a huge negative number:
+            // its weights P = exp(scale * that) are exactly 0, and so is everything it would add to dK and dV.
             if (wave == uu) {
                 int row = row0 + l32;
+                const bool dead = row >= n_rows || u_true >= n_units;
                 row = row < n_rows ? row : n_rows - 1;
-                const float* src = (hf == 0 ? p.neg_lse_s : p.neg_delta) + (int64_t)h * p.total_q + q_base + row;
+                const int64_t idx = (int64_t)h * p.total_q + q_base + row;
+                const float* src = hf == 0 ? p.neg_lse_s + (dead ? (int64_t)p.Hq * p.total_q : idx) : p.neg_delta + idx;
                 copy4_global_to_lds(src, stage + uu * SM::UNIT_BYTES + (size_t)4 * SM::TILE);
             }
         }
     };
-    // copies a wave has issued for one iteration
-    auto wait_previous_iteration = [&]() {
+    // wait until at most the copies this wave has issued for its K most recent iterations are outstanding
+    auto wait_all_but_iterations = [&](auto Kc) {
+        constexpr int K = decltype(Kc)::value;
         if (copies) {
-            if (wave < UPI) wait_vmem_outstanding<COPIES + 1>(); else wait_vmem_outstanding<COPIES>();
+            if (wave < UPI) wait_vmem_outstanding<K * (COPIES + 1)>(); else wait_vmem_outstanding<K * COPIES>();
         } else {
-            if (wave < UPI) wait_vmem_outstanding<1>(); else wait_vmem_outstanding<0>();
+            if (wave < UPI) wait_vmem_outstanding<K>(); else wait_vmem_outstanding<0>();
         }
     };
-    // one (head, 32-row block) unit against the wave's 32 keys
-    auto unit = [&](const unsigned char* ubase, auto ragged, int rows_live) {
+    const std::integral_constant<int, 0> c0{};
+    const std::integral_constant<int, 1> c1{};
+    const std::integral_constant<int, 2> c2i{};
+
+    // The wave's work on one (head, 32-row block) unit against its 32 keys, in four steps that the loop below
+    // interleaves across units: fetch the operands, S and dP, the weights, the two accumulations.
+    struct Operands {
+        bf16x8 qa[NKS], da[NKS];
+        floatx16 S, dP;  // [row (registers)][key (lanes)]
+    };
+    struct Transposed {
+        bf16x8 dot[NDB][2], qt[NDB][2];
+    };
+    auto load_operands = [&](const unsigned char* ubase, Operands& o) {
         const __bf16* Qs = (const __bf16*)ubase;
         const __bf16* dOs = Qs + SM::TILE;
         const float* ss = (const float*)(dOs + SM::TILE);
-        // all LDS operands are requested up front, in the order they are consumed
-        bf16x8 qa[NKS], da[NKS];
 #pragma unroll
         for (int ks = 0; ks < NKS; ks++) {
-            qa[ks] = *(const bf16x8*)(Qs + nat_off[ks]);
-            da[ks] = *(const bf16x8*)(dOs + nat_off[ks]);
+            o.qa[ks] = *(const bf16x8*)(Qs + nat_off[ks]);
+            o.da[ks] = *(const bf16x8*)(dOs + nat_off[ks]);
         }
         // accumulators start from -lse/scale and -delta of their rows (registers 4j..4j+3 hold rows 8j+4hf .. +3)
         floatx4 l4[4], d4[4];
@@ -476,86 +493,118 @@ __global__ __launch_bounds__(NW * 64, D > 64 ? 1 : 2) void bwd_dkdv_kernel(Param
             l4[j] = *(const floatx4*)(ss + 8 * j + 4 * hf);
             d4[j] = *(const floatx4*)(ss + 32 + 8 * j + 4 * hf);
         }
-        floatx16 S = __builtin_shufflevector(__builtin_shufflevector(l4[0], l4[1], 0, 1, 2, 3, 4, 5, 6, 7),
-                                             __builtin_shufflevector(l4[2], l4[3], 0, 1, 2, 3, 4, 5, 6, 7), 0, 1, 2, 3, 4,
-                                             5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
-        floatx16 dP = __builtin_shufflevector(__builtin_shufflevector(d4[0], d4[1], 0, 1, 2, 3, 4, 5, 6, 7),
-                                              __builtin_shufflevector(d4[2], d4[3], 0, 1, 2, 3, 4, 5, 6, 7), 0, 1, 2, 3, 4,
-                                              5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);  // [row (registers)][key (lanes)]
+        o.S = __builtin_shufflevector(__builtin_shufflevector(l4[0], l4[1], 0, 1, 2, 3, 4, 5, 6, 7),
+                                      __builtin_shufflevector(l4[2], l4[3], 0, 1, 2, 3, 4, 5, 6, 7), 0, 1, 2, 3, 4, 5, 6, 7, 8,
+                                      9, 10, 11, 12, 13, 14, 15);
+        o.dP = __builtin_shufflevector(__builtin_shufflevector(d4[0], d4[1], 0, 1, 2, 3, 4, 5, 6, 7),
+                                       __builtin_shufflevector(d4[2], d4[3], 0, 1, 2, 3, 4, 5, 6, 7), 0, 1, 2, 3, 4, 5, 6, 7,
+                                       8, 9, 10, 11, 12, 13, 14, 15);
+    };
+    auto scores = [&](Operands& o) {
 #pragma unroll
         for (int ks = 0; ks < NKS; ks++) {
-            S = mfma32(qa[ks], kf[ks], S);     // S - lse/scale
-            dP = mfma32(da[ks], vf[ks], dP);   // dP - delta
+            o.S = mfma32(o.qa[ks], kf[ks], o.S);     // S - lse/scale
+            o.dP = mfma32(o.da[ks], vf[ks], o.dP);   // dP - delta
         }
-        bf16x8 dot[NDB][2], qt[NDB][2];
+    };
+    auto load_transposed = [&](const unsigned char* ubase, Transposed& f) {
+        const __bf16* Qs = (const __bf16*)ubase;
+        const __bf16* dOs = Qs + SM::TILE;
 #pragma unroll
         for (int db = 0; db < NDB; db++)
 #pragma unroll
             for (int s2 = 0; s2 < 2; s2++) {
-                dot[db][s2] = lds_read_tr_pair(dOs + tr_lo[db] + 16 * s2 * D, dOs + tr_hi[db] + 16 * s2 * D);
-                qt[db][s2] = lds_read_tr_pair(Qs + tr_lo[db] + 16 * s2 * D, Qs + tr_hi[db] + 16 * s2 * D);
+                f.dot[db][s2] = lds_read_tr_pair(dOs + tr_lo[db] + 16 * s2 * D, dOs + tr_hi[db] + 16 * s2 * D);
+                f.qt[db][s2] = lds_read_tr_pair(Qs + tr_lo[db] + 16 * s2 * D, Qs + tr_hi[db] + 16 * s2 * D);
             }
+    };
+    struct Weights {
         bf16x8 pb[2], dsb[2];
+    };
+    auto weights = [&](const Operands& o, Weights& wt, auto ragged) {
 #pragma unroll
         for (int v = 0; v < 16; v++) {
-            float pw = fast_exp2(S[v] * c2);
-            // keys past the history and rows past the end of the user carry no weight
-            if (decltype(ragged)::value) pw = (key_live && 8 * (v / 4) + 4 * hf + (v % 4) < rows_live) ? pw : 0.f;
-            pb[v / 8][v % 8] = (__bf16)pw;
-            dsb[v / 8][v % 8] = (__bf16)(pw * dP[v]);
+            float pw = fast_exp2(o.S[v] * c2);
+            if (decltype(ragged)::value) pw = key_live ? pw : 0.f;  // keys past the history carry no weight
+            wt.pb[v / 8][v % 8] = (__bf16)pw;
+            wt.dsb[v / 8][v % 8] = (__bf16)(pw * o.dP[v]);
         }
-        // dV[key][d] += P^T[key][row] dO[row][d];  dK[key][d] += dS^T[key][row] Q[row][d]
+    };
+    // dV[key][d] += P^T[key][row] dO[row][d];  dK[key][d] += dS^T[key][row] Q[row][d]
+    auto accumulate = [&](const Weights& wt, const Transposed& f) {
 #pragma unroll
         for (int db = 0; db < NDB; db++)
 #pragma unroll
             for (int s2 = 0; s2 < 2; s2++) {
-                dV[db] = mfma32(pb[s2], dot[db][s2], dV[db]);
-                dK[db] = mfma32(dsb[s2], qt[db][s2], dK[db]);
+                dV[db] = mfma32(wt.pb[s2], f.dot[db][s2], dV[db]);
+                dK[db] = mfma32(wt.dsb[s2], f.qt[db][s2], dK[db]);
             }
     };
 
     const std::integral_constant<int, 0> st0{};
     const std::integral_constant<int, 1> st1{};
     const std::integral_constant<int, 2> st2{};
-    // prologue: iteration 0 complete in LDS, iteration 1 in flight
-    if (n_iter > 0) {
-        issue_tiles(0, st0);
-        if (n_iter > 1) {
-            issue_tiles(1, st1);
-            wait_previous_iteration();
-        } else {
-            wait_vmem_outstanding<0>();
-        }
-    }
+    static_assert(UPI == 2, "the loop below is written out for two units per iteration");
+    // prologue: all three stages requested, the first one complete
+    if (n_iter > 0) issue_tiles(0, st0);
+    if (n_iter > 1) issue_tiles(1, st1);
+    if (n_iter > 2) issue_tiles(2, st2);
+    if (n_iter > 2) wait_all_but_iterations(c2i);
+    else if (n_iter > 1) wait_all_but_iterations(c1);
+    else wait_all_but_iterations(c0);
     lds_barrier();
-    // iteration `it` consumes stage St = it % 3 and refills stage (it+2) % 3
-    auto iteration = [&](int it, auto St) {
-        constexpr int st = decltype(St)::value;
-        const unsigned char* base = stage_ptr(St);
-        const bool more2 = it + 2 < n_iter;
-        // stage (it+2)%3 was last read in iteration it-1, which every wave has left
-        if (more2) issue_tiles(it + 2, std::integral_constant<int, (st + 2) % 3>{});
-        if (wave_live) {
-#pragma unroll
-            for (int uu = 0; uu < UPI; uu++) {
-                const int u = it * UPI + uu;
-                if (u < n_units) {
-                    const int rows_live = n_rows - (u / r) * 32;
-                    if (wave_ragged || rows_live < 32)
-                        unit(base + uu * SM::UNIT_BYTES, std::true_type{}, rows_live);
-                    else
-                        unit(base + uu * SM::UNIT_BYTES, std::false_type{}, 32);
-                }
-            }
+
+    // Iteration `it` consumes stage it % 3.  Its barrier sits in the middle of the second unit, after the last LDS read
+    // of the stage: behind it the stage is refilled for iteration it+3 and the operands of iteration it+1 are fetched,
+    // both while the second unit's accumulations keep the matrix unit busy.
+    auto run = [&](auto ragged) {
+        Operands cur;
+        load_operands(stage_ptr(st0), cur);
+        auto iteration = [&](int it, auto St) {
+            constexpr int st = decltype(St)::value;
+            const unsigned char* base = stage_ptr(St);
+            Operands nxt;
+            Transposed f;
+            Weights wt;
+            scores(cur);
+            load_transposed(base, f);
+            weights(cur, wt, ragged);
+            load_operands(base + SM::UNIT_BYTES, nxt);
+            accumulate(wt, f);
+            scores(nxt);
+            load_transposed(base + SM::UNIT_BYTES, f);
+            weights(nxt, wt, ragged);
+            // copies of iteration it+1 must have landed; those of it+2 may stay in flight
+            if (it + 2 < n_iter) wait_all_but_iterations(c1); else wait_all_but_iterations(c0);
+            lds_barrier();
+            if (it + 3 < n_iter) issue_tiles(it + 3, St);
+            // (behind the last iteration this reads a stage that holds nothing new; the values are not used)
+            load_operands(stage_ptr(std::integral_constant<int, (st + 1) % 3>{}), cur);
+            accumulate(wt, f);
+        };
+        for (int it = 0; it < n_iter; it += 3) {
+            iteration(it, st0);
+            if (it + 1 < n_iter) iteration(it + 1, st1);
+            if (it + 2 < n_iter) iteration(it + 2, st2);
         }
-        // the copies of iteration it+1 (issued one iteration ago) must have landed; those of it+2 may stay in flight
-        if (more2) wait_previous_iteration(); else wait_vmem_outstanding<0>();
-        lds_barrier();
     };
-    for (int it = 0; it < n_iter; it += 3) {
-        iteration(it, st0);
-        if (it + 1 < n_iter) iteration(it + 1, st1);
-        if (it + 2 < n_iter) iteration(it + 2, st2);
+    // a wave past the history only helps staging: same waits, same barriers, same copies
+    auto run_idle = [&]() {
+        auto iteration = [&](int it, auto St) {
+            if (it + 2 < n_iter) wait_all_but_iterations(c1); else wait_all_but_iterations(c0);
+            lds_barrier();
+            if (it + 3 < n_iter) issue_tiles(it + 3, St);
+        };
+        for (int it = 0; it < n_iter; it += 3) {
+            iteration(it, st0);
+            if (it + 1 < n_iter) iteration(it + 1, st1);
+            if (it + 2 < n_iter) iteration(it + 2, st2);
+        }
+    };
+    if (n_iter > 0) {
+        if (!wave_live) run_idle();
+        else if (wave_ragged) run(std::true_type{});
+        else run(std::false_type{});
     }
 
     // write the wave's 32 key rows: lanes cover 32 consecutive d
