@@ -421,37 +421,61 @@ __global__ __launch_bounds__(NW * 64, D > 64 ? 1 : 2) void bwd_dkdv_kernel(Param
 
     // Q and dO tiles of iteration `it` -> stage it % NSTAGE.  Copy j of a tile covers rows j*RPI .. j*RPI+RPI-1:
     // lane i lands at chunk position i % CPR of row j*RPI + i / CPR, so it fetches the chunk that belongs there.
-    auto issue_tiles = [&](int it, auto St) {
-        unsigned char* stage = stage_ptr(St);
+    // The calls come in the order it = 0, 1, 2, ...; the unit the next call starts with is kept in (iss_rb, iss_hh).
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    uint32_t tile_voff[IPW];  // byte offset of the lane's chunk from the first element of (row0, head h)
+#pragma unroll
+    for (int jj = 0; jj < IPW; jj++) {
+        const int trow = (wave + jj * NW) * RPI + lane / CPR;
+        tile_voff[jj] = (uint32_t)((trow * p.Hq * D + (((lane % CPR) ^ swizzle<D>(trow)) << 3)) * 2);
+    }
+    const float* stat_lane = (hf == 0 ? p.neg_lse_s : p.neg_delta) + q_base + l32;
+    int iss_rb = 0, iss_hh = 0;
+    auto issue_tiles = [&](auto St) {
+        const uint32_t stage = lds_address(stage_ptr(St));
 #pragma unroll
         for (int uu = 0; uu < UPI; uu++) {
-            const int u_true = it * UPI + uu;
-            const int u = u_true < n_units ? u_true : n_units - 1;  // a missing unit repeats the last one, with no weight
-            const int row0 = (u / r) * 32, h = g * r + u % r;
+            // a unit past the last one repeats the last one, with no weight
+            const bool past = iss_rb >= n_rb;
+            const int rb = past ? n_rb - 1 : iss_rb, hh = past ? r - 1 : iss_hh;
+            const int row0 = rb * 32, h = g * r + hh;
+            const bool whole = !past && row0 + 32 <= n_rows;  // every row exists: no per-lane address arithmetic
+            const uint32_t unit = stage + uu * (uint32_t)SM::UNIT_BYTES;
+            const int64_t ubase = ((q_base + row0) * p.Hq + h) * (int64_t)D;
+            if (whole) {
 #pragma unroll
-            for (int jj = 0; jj < (copies ? IPW : 0); jj++) {
-                const int j = wave + jj * NW;   // < IPT by construction
-                const int trow = j * RPI + lane / CPR;
-                int row = row0 + trow;
-                row = row < n_rows ? row : n_rows - 1;  // rows past the end repeat the last row, with no weight
-                const int chunk = (lane % CPR) ^ swizzle<D>(trow);
-                const int64_t off = ((q_base + row) * p.Hq + h) * D + chunk * 8;
-                unsigned char* dst = stage + uu * SM::UNIT_BYTES + (size_t)j * 1024;
-                copy16_global_to_lds((const __bf16*)p.q + off, dst);
-                copy16_global_to_lds((const __bf16*)p.dout + off, dst + (size_t)SM::TILE * 2);
+                for (int jj = 0; jj < (copies ? IPW : 0); jj++) {
+                    const uint32_t dst = unit + (uint32_t)(wave_u + jj * NW) * 1024u;
+                    copy16_global_to_lds_at((const __bf16*)p.q + ubase, tile_voff[jj], dst);
+                    copy16_global_to_lds_at((const __bf16*)p.dout + ubase, tile_voff[jj], dst + (uint32_t)SM::TILE * 2u);
+                }
+                if (wave_u == uu) copy4_global_to_lds_at(stat_lane + ((int64_t)h * p.total_q + row0), unit + 4u * (uint32_t)SM::TILE);
+            } else {
+#pragma unroll
+                for (int jj = 0; jj < (copies ? IPW : 0); jj++) {
+                    const int trow = (wave + jj * NW) * RPI + lane / CPR;
+                    int row = row0 + trow;
+                    row = row < n_rows ? row : n_rows - 1;  // rows past the end repeat the last row, with no weight
+                    const int chunk = (lane % CPR) ^ swizzle<D>(trow);
+                    const int64_t off = ((q_base + row) * p.Hq + h) * D + chunk * 8;
+                    const uint32_t dst = unit + (uint32_t)(wave_u + jj * NW) * 1024u;
+                    copy16_global_to_lds_at((const __bf16*)p.q + off, dst);
+                    copy16_global_to_lds_at((const __bf16*)p.dout + off, dst + (uint32_t)SM::TILE * 2u);
+                }
+                // A row that does not exist starts from the sentinel behind the -lse/scale array, a huge negative
+                // number: its weights P = exp(scale * that) are exactly 0, and so is all it would add to dK and dV.
+                if (wave_u == uu) {
+                    int row = row0 + l32;
+                    const bool dead = past || row >= n_rows;
+                    row = row < n_rows ? row : n_rows - 1;
+                    const int64_t idx = (int64_t)h * p.total_q + q_base + row;
+                    const float* src = hf == 0 ? p.neg_lse_s + (dead ? (int64_t)p.Hq * p.total_q : idx) : p.neg_delta + idx;
+                    copy4_global_to_lds_at(src, unit + 4u * (uint32_t)SM::TILE);
+                }
             }
-            // Row statistics of the unit, copied by wave uu: lanes 0..31 fetch -lse/scale, lanes 32..63 -delta of row
-            // lane % 32.  These are the values the S and dP accumulators start from, so that the products come out
-            // as S - lse/scale and dP - delta.  A row that does not exist (past the end of the user, or a whole unit
-            // past the last one) starts from the sentinel behind the -lse/scale array instead, a huge negative number:
-            // its weights P = exp(scale * that) are exactly 0, and so is everything it would add to dK and dV.
-            if (wave == uu) {
-                int row = row0 + l32;
-                const bool dead = row >= n_rows || u_true >= n_units;
-                row = row < n_rows ? row : n_rows - 1;
-                const int64_t idx = (int64_t)h * p.total_q + q_base + row;
-                const float* src = hf == 0 ? p.neg_lse_s + (dead ? (int64_t)p.Hq * p.total_q : idx) : p.neg_delta + idx;
-                copy4_global_to_lds(src, stage + uu * SM::UNIT_BYTES + (size_t)4 * SM::TILE);
+            if (!past && ++iss_hh == r) {
+                iss_hh = 0;
+                iss_rb++;
             }
         }
     };
@@ -546,9 +570,9 @@ __global__ __launch_bounds__(NW * 64, D > 64 ? 1 : 2) void bwd_dkdv_kernel(Param
     const std::integral_constant<int, 2> st2{};
     static_assert(UPI == 2, "the loop below is written out for two units per iteration");
     // prologue: all three stages requested, the first one complete
-    if (n_iter > 0) issue_tiles(0, st0);
-    if (n_iter > 1) issue_tiles(1, st1);
-    if (n_iter > 2) issue_tiles(2, st2);
+    if (n_iter > 0) issue_tiles(st0);
+    if (n_iter > 1) issue_tiles(st1);
+    if (n_iter > 2) issue_tiles(st2);
     if (n_iter > 2) wait_all_but_iterations(c2i);
     else if (n_iter > 1) wait_all_but_iterations(c1);
     else wait_all_but_iterations(c0);
@@ -577,7 +601,7 @@ __global__ __launch_bounds__(NW * 64, D > 64 ? 1 : 2) void bwd_dkdv_kernel(Param
             // copies of iteration it+1 must have landed; those of it+2 may stay in flight
             if (it + 2 < n_iter) wait_all_but_iterations(c1); else wait_all_but_iterations(c0);
             lds_barrier();
-            if (it + 3 < n_iter) issue_tiles(it + 3, St);
+            if (it + 3 < n_iter) issue_tiles(St);
             // (behind the last iteration this reads a stage that holds nothing new; the values are not used)
             load_operands(stage_ptr(std::integral_constant<int, (st + 1) % 3>{}), cur);
             accumulate(wt, f);
@@ -593,7 +617,7 @@ __global__ __launch_bounds__(NW * 64, D > 64 ? 1 : 2) void bwd_dkdv_kernel(Param
         auto iteration = [&](int it, auto St) {
             if (it + 2 < n_iter) wait_all_but_iterations(c1); else wait_all_but_iterations(c0);
             lds_barrier();
-            if (it + 3 < n_iter) issue_tiles(it + 3, St);
+            if (it + 3 < n_iter) issue_tiles(St);
         };
         for (int it = 0; it < n_iter; it += 3) {
             iteration(it, st0);

@@ -125,6 +125,24 @@ __device__ inline void copy4_global_to_lds(const void* global_lane_ptr, void* ld
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" : : "s"(base), "v"(global_lane_ptr) : "memory");
 }
 
+// The same copies with the LDS destination given as a byte address inside LDS (wave-uniform), which spares the
+// address-space conversion of a generic pointer; lds_address() of a pointer into a __shared__ array is that address.
+__device__ inline uint32_t lds_address(const void* p) { return (uint32_t)(uintptr_t)(HTA_LDS const void*)p; }
+
+__device__ inline void copy16_global_to_lds_at(const void* global_lane_ptr, uint32_t lds_wave_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_wave_addr), "v"(global_lane_ptr) : "memory");
+}
+
+__device__ inline void copy4_global_to_lds_at(const void* global_lane_ptr, uint32_t lds_wave_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" : : "s"(lds_wave_addr), "v"(global_lane_ptr) : "memory");
+}
+
+// 16-byte copy whose global address is a wave-uniform base plus a per-lane unsigned byte offset: no address
+// arithmetic on the vector unit at all when the per-lane offsets are loop-invariant.
+__device__ inline void copy16_global_to_lds_at(const void* uniform_base, uint32_t lane_byte_offset, uint32_t lds_wave_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_wave_addr), "v"(lane_byte_offset), "s"(uniform_base) : "memory");
+}
+
 // wait until at most N vector-memory operations of this wave are still outstanding (N < 64)
 template <int N>
 __device__ inline void wait_vmem_outstanding() {
