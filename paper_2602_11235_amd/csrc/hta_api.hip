@@ -26,7 +26,7 @@ struct Workspace {
 };
 
 // Layout of the caller's workspace (bf16 path; the fp32 debug path needs none):
-//   order [batch] int32   users by decreasing tile count, rebuilt by every call
+//   work counters (256 bytes) and order [batch] int32, users by decreasing tile count; both rebuilt by every call
 //   -delta and -lse/scale, [Hq][total_q] f32 each, the latter followed by one sentinel element   backward only
 Workspace plan_workspace(int dtype, int is_bwd, int32_t batch, int64_t total_q, int32_t Hq) {
     Workspace w{0, 0, 0, 0};
@@ -145,9 +145,10 @@ int mtfm_hta_fwd(const void* q, const void* k, const void* v, void* out, float* 
     hipStream_t s = (hipStream_t)stream;
     hipError_t e = hipSuccess;
     if (dtype == MTFM_HTA_BF16) {
-        int32_t* order = (int32_t*)((char*)workspace + w.order_off);
-        e = hta::launch_schedule(p, order, s);
-        p.order = order;
+        void* region = (char*)workspace + w.order_off;
+        e = hta::launch_schedule(p, region, s);
+        p.order = hta::schedule_order(region);
+        p.queue = hta::schedule_queue(region, 0);  // the launchers add the kernel kind
     }
     if (e == hipSuccess) e = dtype == MTFM_HTA_FP32 ? hta::launch_fwd_fp32(p, s) : hta::launch_fwd_bf16(p, s);
     if (e != hipSuccess) return fail(MTFM_HTA_ERR_LAUNCH, "forward launch failed: %s", hipGetErrorString(e));
@@ -186,9 +187,10 @@ int mtfm_hta_bwd(const void* dout, const void* q, const void* k, const void* v, 
     hipStream_t s = (hipStream_t)stream;
     hipError_t e = hipSuccess;
     if (dtype == MTFM_HTA_BF16) {
-        int32_t* order = (int32_t*)((char*)workspace + w.order_off);
-        e = hta::launch_schedule(p, order, s);
-        p.order = order;
+        void* region = (char*)workspace + w.order_off;
+        e = hta::launch_schedule(p, region, s);
+        p.order = hta::schedule_order(region);
+        p.queue = hta::schedule_queue(region, 0);  // the launchers add the kernel kind
     }
     if (e == hipSuccess) e = dtype == MTFM_HTA_FP32 ? hta::launch_bwd_fp32(p, s) : hta::launch_bwd_bf16(p, s);
     if (e != hipSuccess) return fail(MTFM_HTA_ERR_LAUNCH, "backward launch failed: %s", hipGetErrorString(e));

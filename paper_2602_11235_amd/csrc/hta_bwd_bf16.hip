@@ -334,7 +334,7 @@ struct DkdvSmem {
 // One workgroup per (user, kv head, tile of NW*32 history keys).  Q and dO tiles travel global -> LDS directly
 // (no register stop-over), two iterations ahead of their use.
 template <int D, int NW>
-__global__ __launch_bounds__(NW * 64, D > 64 ? 1 : 2) void bwd_dkdv_kernel(Params p, int tpg) {
+__global__ __launch_bounds__(NW * 64, D > 64 ? 1 : 2) void bwd_dkdv_kernel(Params p, int tpg, unsigned per_xcd) {
     using SM = DkdvSmem<D, NW>;
     constexpr int UPI = SM::UPI, NSTAGE = SM::NSTAGE;
     constexpr int NKS = D / 16, NDB = D / 32;
@@ -358,8 +358,12 @@ __global__ __launch_bounds__(NW * 64, D > 64 ? 1 : 2) void bwd_dkdv_kernel(Param
         return stage2;
     };
 
+    __shared__ int s_item;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
-    const WorkItem w = decode_work(blockIdx.x, p.batch * p.Hkv, p.Hkv, tpg);
+
+    // one work item: a (user, kv head, key tile) triple
+    auto process = [&](unsigned id) {
+    const WorkItem w = decode_work(id, p.batch * p.Hkv, p.Hkv, tpg);
     if (!w.valid) return;
     const int b = scheduled_user(p, w.user_slot), g = w.y;
     const int L = p.hist_len[b], T = p.n_targets[b];
@@ -648,6 +652,21 @@ __global__ __launch_bounds__(NW * 64, D > 64 ? 1 : 2) void bwd_dkdv_kernel(Param
             }
         }
     }
+    };  // process
+
+    // persistent workgroup: items come from the work counters until all lists are exhausted
+    const int xcd = blockIdx.x % N_XCD;
+    unsigned taken = 0;
+    if (tid == 0) taken = queue_take_ahead(p.queue, xcd);
+    for (;;) {
+        if (tid == 0) s_item = queue_resolve(p.queue, xcd, taken, per_xcd);
+        __syncthreads();
+        const int id = s_item;
+        if (id < 0) break;
+        if (tid == 0) taken = queue_take_ahead(p.queue, xcd);
+        process((unsigned)id);
+        __syncthreads();  // the stages and s_item are free again
+    }
 }
 
 int gcd_i(int a, int b) { return b == 0 ? a : gcd_i(b, a % b); }
@@ -671,9 +690,13 @@ template <int D, int NW>
 hipError_t launch_dkdv(const Params& p, hipStream_t s) {
     if (p.max_hist <= 0) return hipSuccess;
     const int64_t n_kt = (p.max_hist + NW * 32 - 1) / (NW * 32);
-    const int64_t n_blocks = work_grid((int64_t)p.batch * p.Hkv, n_kt);
-    if (n_blocks >= (1ll << 31)) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((bwd_dkdv_kernel<D, NW>), dim3((unsigned)n_blocks), dim3(NW * 64), 0, s, p, (int)n_kt);
+    const int64_t n_items = work_grid((int64_t)p.batch * p.Hkv, n_kt);
+    if (n_items >= (1ll << 31)) return hipErrorInvalidValue;
+    const int64_t resident = resident_workgroups<bwd_dkdv_kernel<D, NW>>(NW * 64);
+    Params pk = p;
+    pk.queue = p.queue + QUEUE_DKDV * N_XCD;
+    hipLaunchKernelGGL((bwd_dkdv_kernel<D, NW>), dim3((unsigned)(n_items < resident ? n_items : resident)), dim3(NW * 64), 0, s,
+                       pk, (int)n_kt, (unsigned)(n_items / N_XCD));
     return hipGetLastError();
 }
 

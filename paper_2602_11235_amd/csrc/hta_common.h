@@ -34,6 +34,7 @@ struct Params {
     float* neg_delta;     // [Hq][total_q]   -<dout_i, out_i>
     float* neg_lse_s;     // [Hq][total_q]   -lse_i / scale: what the S accumulators of the dK/dV pass start from
     const int32_t* order; // [batch] users by decreasing tile count (bf16 path), or null = identity
+    int32_t* queue;       // [N_XCD] work counters of the kernel being launched (bf16 path), zero when it starts
 };
 
 // number of query rows a user can have at most, from the host-known bounds
@@ -50,9 +51,15 @@ bool bf16_supported(int32_t d, int32_t Hq, int32_t Hkv);
 // MTFM_HTA_KERNEL_* values
 void timing_begin(int kind, hipStream_t s);
 void timing_end(int kind, hipStream_t s);
-// user order of the launch (blockIdx.z -> user): long histories first
+// The schedule region at the head of the workspace: work counters (one per kernel kind and XCD, 256 bytes in all),
+// then the user order of the launch, long histories first.  launch_schedule() zeroes the former and builds the latter.
+constexpr int N_XCD = 8;
+constexpr int QUEUE_DKDV = 0;  // kernel kinds that take their work from counters
+constexpr int QUEUE_WORDS = 64;
 size_t schedule_bytes(int32_t batch);
-hipError_t launch_schedule(const Params& p, int32_t* order, hipStream_t s);
+hipError_t launch_schedule(const Params& p, void* region, hipStream_t s);
+inline int32_t* schedule_order(void* region) { return (int32_t*)region + QUEUE_WORDS; }
+inline int32_t* schedule_queue(void* region, int kind) { return (int32_t*)region + kind * N_XCD; }
 __device__ inline int scheduled_user(const Params& p, int slot) { return p.order ? p.order[slot] : slot; }
 // Placement of workgroups.  Work is a list of groups (user slot, y) -- y = kv head (x head chunk) -- each with up
 // to `tpg` tiles that share operands (the K/V of the group, or its Q/dO).  The chip has 8 XCDs, each with its own
@@ -60,7 +67,6 @@ __device__ inline int scheduled_user(const Params& p, int slot) { return p.order
 // on one XCD (its tiles are consecutive slots there, so they also run close in time), and groups are dealt to the
 // XCDs round-robin in schedule order, which keeps the long-first order inside every XCD.  Only locality depends
 // on the round-robin assumption, never correctness.
-constexpr int N_XCD = 8;
 struct WorkItem {
     int user_slot, y, tile;
     bool valid;
@@ -77,6 +83,39 @@ __device__ inline WorkItem decode_work(unsigned id, int n_groups, int ny, int tp
     return w;
 }
 inline int64_t work_grid(int64_t n_groups, int64_t tpg) { return ((n_groups + N_XCD - 1) / N_XCD) * N_XCD * tpg; }
+
+// Work distribution for kernels with long work items (the dK/dV pass: tens of microseconds per item).  The hardware
+// hands the workgroups of a grid to the shader engines in a fixed rotation, whatever each has left to do, so with items
+// of unequal length (jagged users) whole compute units run dry while others queue up: a fifth of the chip on the
+// paper's length mix.  Such a kernel launches only as many workgroups as the chip holds at once, and each takes work
+// item after work item from a counter (kernels with short items lose more to the hand-over than they gain): XCD x serves the ids x, x + 8, x + 16, ... (which keeps a group's tiles on one L2, as
+// above), in order, through counters[x]; a workgroup whose own XCD has nothing left helps the others.  The loop ends
+// for a workgroup once every counter has passed the end of its list, which every workgroup reaches.
+//   thread 0:  take the next slot of the own XCD in advance (one atomic, its latency hidden behind an item) ...
+__device__ inline unsigned queue_take_ahead(int32_t* counters, int xcd) { return atomicAdd((unsigned*)&counters[xcd], 1u); }
+//   ... and turn it into a work id, or -1 when all lists are exhausted
+__device__ inline int queue_resolve(int32_t* counters, int xcd, unsigned taken, unsigned per_xcd) {
+    if (taken < per_xcd) return (int)(taken * N_XCD + xcd);
+    for (int q = 1; q < N_XCD; q++) {
+        const int x = (xcd + q) % N_XCD;
+        const unsigned slot = atomicAdd((unsigned*)&counters[x], 1u);
+        if (slot < per_xcd) return (int)(slot * N_XCD + x);
+    }
+    return -1;
+}
+// workgroups of `Kernel` (at `threads` threads, no dynamic LDS) that the current device holds at once
+template <auto Kernel>
+inline int resident_workgroups(int threads) {
+    static int cached = 0;
+    if (cached == 0) {
+        int dev = 0, n_cu = 0, per_cu = 0;
+        if (hipGetDevice(&dev) != hipSuccess) return 256;
+        if (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 256;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, Kernel, threads, 0) != hipSuccess) return 256;
+        cached = n_cu * (per_cu > 0 ? per_cu : 1);
+    }
+    return cached;
+}
 // fill `n` 32-bit words with zero (a kernel, so that a caller may capture the call in a HIP graph)
 hipError_t launch_zero_words(void* ptr, size_t n_words, hipStream_t s);
 

@@ -21,9 +21,10 @@ __device__ inline float user_cost(const Params& p, int b) {
 }
 
 // order[i] = user with the i-th largest cost; ties broken by user index, so the result is unique
-__global__ __launch_bounds__(SCHED_THREADS) void schedule_rank_kernel(Params p, int32_t* order) {
+__global__ __launch_bounds__(SCHED_THREADS) void schedule_rank_kernel(Params p, int32_t* counters, int32_t* order) {
     __shared__ float cost[RANK_SORT_MAX];
     const int B = p.batch;
+    if (threadIdx.x < QUEUE_WORDS) counters[threadIdx.x] = 0;
     for (int b = threadIdx.x; b < B; b += SCHED_THREADS) cost[b] = user_cost(p, b);
     __syncthreads();
     for (int b = threadIdx.x; b < B; b += SCHED_THREADS) {
@@ -39,10 +40,11 @@ __global__ __launch_bounds__(SCHED_THREADS) void schedule_rank_kernel(Params p, 
 
 // Large batches: users fall into N_BUCKETS cost classes (by cost / max possible cost); classes are laid out
 // by decreasing cost, users inside a class in arrival order of the atomics (any order is a valid schedule).
-__global__ __launch_bounds__(SCHED_THREADS) void schedule_bucket_kernel(Params p, int32_t* order) {
+__global__ __launch_bounds__(SCHED_THREADS) void schedule_bucket_kernel(Params p, int32_t* counters, int32_t* order) {
     __shared__ int count[N_BUCKETS];
     __shared__ int start[N_BUCKETS];
     const int B = p.batch;
+    if (threadIdx.x < QUEUE_WORDS) counters[threadIdx.x] = 0;
     const float rows_max = (float)(p.layer == 0 ? (int64_t)p.max_hist + p.max_targets : (int64_t)p.max_targets);
     const float inv = (float)(N_BUCKETS - 1) / fmaxf(rows_max * (float)p.max_hist, 1.f);
     for (int i = threadIdx.x; i < N_BUCKETS; i += SCHED_THREADS) count[i] = 0;
@@ -68,14 +70,18 @@ __global__ __launch_bounds__(SCHED_THREADS) void schedule_bucket_kernel(Params p
 
 }  // namespace
 
-size_t schedule_bytes(int32_t batch) { return (((size_t)batch * sizeof(int32_t)) + 255) & ~(size_t)255; }
+size_t schedule_bytes(int32_t batch) {
+    return QUEUE_WORDS * sizeof(int32_t) + ((((size_t)batch * sizeof(int32_t)) + 255) & ~(size_t)255);
+}
 
-hipError_t launch_schedule(const Params& p, int32_t* order, hipStream_t s) {
+hipError_t launch_schedule(const Params& p, void* region, hipStream_t s) {
     if (p.batch <= 0) return hipSuccess;
+    int32_t* counters = (int32_t*)region;
+    int32_t* order = schedule_order(region);
     if (p.batch <= RANK_SORT_MAX)
-        hipLaunchKernelGGL(schedule_rank_kernel, dim3(1), dim3(SCHED_THREADS), 0, s, p, order);
+        hipLaunchKernelGGL(schedule_rank_kernel, dim3(1), dim3(SCHED_THREADS), 0, s, p, counters, order);
     else
-        hipLaunchKernelGGL(schedule_bucket_kernel, dim3(1), dim3(SCHED_THREADS), 0, s, p, order);
+        hipLaunchKernelGGL(schedule_bucket_kernel, dim3(1), dim3(SCHED_THREADS), 0, s, p, counters, order);
     return hipGetLastError();
 }
 

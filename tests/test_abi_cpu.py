@@ -27,10 +27,12 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_workspace_bytes_is_host_arithmetic():
-    assert hta.mtfm_hta_workspace_bytes(hta.LAYER_FULL, hta.BF16, False, 4, 1000, 1000, 512, 64, 8, 2, 64) == 256
+    # forward: the work counters (256 bytes) and the user order (4 users -> one 256-byte block)
+    assert hta.mtfm_hta_workspace_bytes(hta.LAYER_FULL, hta.BF16, False, 4, 1000, 1000, 512, 64, 8, 2, 64) == 512
     assert hta.mtfm_hta_workspace_bytes(hta.LAYER_FULL, hta.FP32, False, 4, 1000, 1000, 512, 64, 8, 2, 64) == 0
     n = hta.mtfm_hta_workspace_bytes(hta.LAYER_FULL, hta.BF16, True, 4, 1000, 1000, 512, 64, 8, 2, 64)
-    assert n >= 1000 * 8 * 4 and n % 256 == 0
+    # backward: two float rows per (head, query row) on top of that, one of them with a sentinel element
+    assert n >= 512 + 2 * 1000 * 8 * 4 and n % 256 == 0
     assert hta.mtfm_hta_workspace_bytes(hta.LAYER_FULL, hta.FP32, True, 4, 1000, 1000, 512, 64, 8, 2, 16) == 0
     with pytest.raises(hta.HtaError):
         hta.mtfm_hta_workspace_bytes(hta.LAYER_FULL, hta.BF16, True, 4, 1000, 1000, 512, 64, 8, 3, 64)
