@@ -70,6 +70,23 @@ def cpu_baseline(case, inputs, budget_s: float):
     }
 
 
+def recorded_traffic(workload: str, kernel: str):
+    """HBM bytes per launch of `kernel` on `workload`, as recorded by the committed rocprofv3 counter summary
+    (FETCH_SIZE / WRITE_SIZE cannot be read from inside this process); None when there is no record."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", f"{workload.lower()}_hta_fwd_bwd_kernels.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                parts = line.split()
+                if len(parts) == 4 and parts[0] == "TRAFFIC" and parts[1] == kernel:
+                    kv = dict(x.split("=") for x in parts[2:])
+                    return {"read_bytes": int(kv["read_bytes"]), "write_bytes": int(kv["write_bytes"]),
+                            "source": os.path.relpath(path, os.path.dirname(os.path.abspath(__file__)))}
+    except (OSError, ValueError, KeyError):
+        pass
+    return None
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -165,6 +182,12 @@ def main() -> int:
                     "unit": "TFLOP/s", "frac": ach / BF16_MFMA_PEAK_TFLOPS, "traffic": None,
                     "avg_kernel_ms": kernels[dominant]["avg_ms"],
                     "algorithmic_flops_per_launch": flops[dominant]}
+        measured = recorded_traffic(cfg.name, dominant)
+        if measured is not None:
+            roofline["traffic"] = measured["read_bytes"] + measured["write_bytes"]
+            roofline["traffic_note"] = (f"HBM bytes per launch (read {measured['read_bytes']}, written "
+                                        f"{measured['write_bytes']}) from the rocprofv3 counter runs recorded in "
+                                        f"{measured['source']}; not measured by this run")
 
     result = {
         "metric": "HTA fwd+bwd TFLOP/s & samples/s at B=256,L=1024,T=64; % of bf16 MFMA peak",
