@@ -65,12 +65,14 @@ enum { MTFM_HTA_LAYER_FULL = 0, MTFM_HTA_LAYER_TARGET = 1 };
 
 /*
  * Bytes of device workspace a call with these sizes needs (0 is possible).  Pure host arithmetic.
- * The bf16 path keeps there the user schedule it builds on the device at the start of every call
- * (users ordered by decreasing number of attention tiles, from hist_len / n_targets) and, for the
- * backward pass, delta = <dout, out> per query row.
+ * The bf16 path keeps there what it builds on the device at the start of every call -- the work
+ * counters of its persistent kernels and the user schedule (users ordered by decreasing number of
+ * attention tiles, from hist_len / n_targets) -- and, for the backward pass, two float32 values per
+ * (query head, query row): -delta = -<dout, out> and -lse / softmax_scale.
  * is_bwd = 0 for mtfm_hta_fwd, 1 for mtfm_hta_bwd.  Returns (size_t)-1 for invalid arguments.
  * The workspace must be 256-byte aligned; its contents are undefined before and after a call and it
- * may be reused by the next call on the same stream.
+ * may be reused by the next call on the same stream.  Two calls that run at the same time (on
+ * different streams) need a workspace each.
  */
 MTFM_HTA_API size_t mtfm_hta_workspace_bytes(int layer, int dtype, int is_bwd, int32_t batch, int64_t total_q,
                                 int64_t total_kv, int32_t max_hist, int32_t max_targets, int32_t Hq,
