@@ -18,6 +18,7 @@
 #include "../../include/mtfm_hta.h"
 #include "hta_common.h"
 #include "hta_mfma.h"
+#include "hta_tiles.h"
 
 namespace hta {
 namespace {
@@ -25,23 +26,17 @@ namespace {
 constexpr int BN = 64;  // keys per LDS tile
 constexpr float RESCALE_SLACK = 8.f;  // log2 units a row's logits may exceed its softmax reference before a rescale
 
-template <int D>
-struct Tile {
-    static constexpr int KS = D + 8;  // K row pitch (elements): 16-byte pad keeps 16-byte row reads conflict-free
-    static constexpr int VS = D + 8;  // V row pitch
-    static constexpr int BUF_ELEMS = BN * KS + BN * VS;   // one K tile + one V tile
-    static constexpr int LDS_ELEMS = 2 * BUF_ELEMS;       // double buffered
-};
-
 template <int D, int RB, int NW>
 __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb, int n_hc, int tpg) {
-    constexpr int NT = NW * 64;
-    constexpr int KS = Tile<D>::KS, VS = Tile<D>::VS;
-    constexpr int CPR = D / 8;                     // 16-byte chunks per K/V row
-    constexpr int NCH = BN * CPR;                  // chunks per tile
-    constexpr int CH = (NCH + NT - 1) / NT;        // chunks per thread
+    using ST = KvStage<D, NW>;
     constexpr int NKS = D / 16, NDB = D / 32, NKB = BN / 32;
-    __shared__ __attribute__((aligned(16))) __bf16 smem[Tile<D>::LDS_ELEMS];
+    static_assert(ST::BN == BN, "tile height");
+    // NSTAGE stages of [K tile][V tile], filled by asynchronous global -> LDS copies NSTAGE-1 tiles ahead of their use
+    // (two ahead, except for d = 128 where a third stage would cost the second workgroup of the CU).  The compiler
+    // never sees a store into this array (the copies are issued from inline assembly), so it neither orders LDS reads
+    // against them nor drains them; the counted waits and barriers below do that.
+    constexpr int NSTAGE = D <= 64 ? 3 : 2, AHEAD = NSTAGE - 1;
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[NSTAGE * ST::BYTES];
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
     const WorkItem w = decode_work(blockIdx.x, p.batch * p.Hkv * n_hc, p.Hkv * n_hc, tpg);
@@ -88,38 +83,17 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb,
     }
 
     const int n_kt = (L + BN - 1) / BN;
-    uint4 kreg[CH], vreg[CH];
-    auto load_tile = [&](int t) {
-#pragma unroll
-        for (int i = 0; i < CH; i++) {
-            const int c = tid + i * NT;
-            const int key = t * BN + c / CPR, dc = c % CPR;
-            kreg[i] = make_uint4(0, 0, 0, 0);
-            vreg[i] = make_uint4(0, 0, 0, 0);
-            if (c < NCH && key < L) {  // keys past the history are zero-filled (their weight is 0)
-                const int64_t off = ((kv_base + key) * p.Hkv + g) * D + dc * 8;
-                kreg[i] = *(const uint4*)(kg + off);
-                vreg[i] = *(const uint4*)(vg + off);
-            }
-        }
-    };
-    auto store_tile = [&](int buf) {
-        __bf16* Kd = smem + buf * Tile<D>::BUF_ELEMS;
-        __bf16* Vd = Kd + BN * KS;
-#pragma unroll
-        for (int i = 0; i < CH; i++) {
-            const int c = tid + i * NT;
-            if (c < NCH) {
-                const int key = c / CPR, dc = c % CPR;
-                *(uint4*)(Kd + key * KS + dc * 8) = kreg[i];
-                *(uint4*)(Vd + key * VS + dc * 8) = vreg[i];
-            }
-        }
-    };
+    int nat[NKS], tlo[NDB], thi[NDB];  // per-lane element offsets of the operand fragments inside a swizzled tile
+    natural_offsets<D>(nat, lane);
+    transposed_offsets<D>(tlo, thi, lane);
+    uint32_t voff[ST::COPIES];
+    ST::lane_offsets(voff, p.Hkv, wave, lane);
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const uint32_t smem_addr = lds_address(smem);
 
     // One online-softmax step over a 32-key sub-tile.  `n_live` = number of keys of the sub-tile that are
     // inside the history (32 except in the ragged last tile).
-    auto subtile = [&](const __bf16* Ks, const __bf16* Vs, int kb, int n_live) {
+    auto subtile = [&](const __bf16* Ks, const __bf16* Vs, int n_live) {  // Ks, Vs: first row of the sub-tile
         // S^T[key][row] = sum_d K[key][d] Q[row][d]
         floatx16 S[RB];
 #pragma unroll
@@ -128,7 +102,7 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb,
             for (int v = 0; v < 16; v++) S[rb][v] = 0.f;
 #pragma unroll
         for (int ks = 0; ks < NKS; ks++) {
-            const bf16x8 kf = *(const bf16x8*)(Ks + (kb * 32 + l32) * KS + ks * 16 + 8 * hf);
+            const bf16x8 kf = *(const bf16x8*)(Ks + nat[ks]);
 #pragma unroll
             for (int rb = 0; rb < RB; rb++) S[rb] = mfma32(kf, qf[rb][ks], S[rb]);
         }
@@ -178,32 +152,48 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb,
         for (int db = 0; db < NDB; db++)
 #pragma unroll
             for (int s2 = 0; s2 < 2; s2++) {
-                const bf16x8 vf = lds_read_tr_8(Vs, VS, kb * 32 + 16 * s2 + 4 * hf, db * 32 + 16 * ((lane >> 4) & 1), lane);
+                const bf16x8 vf = lds_read_tr_pair(Vs + 16 * s2 * D + tlo[db], Vs + 16 * s2 * D + thi[db]);
 #pragma unroll
                 for (int rb = 0; rb < RB; rb++) O[rb][db] = mfma32(vf, pf[rb][s2], O[rb][db]);
             }
     };
 
-    if (n_kt > 0) {
-        load_tile(0);
-        store_tile(0);
-        __syncthreads();
-    }
-    // Q fragments must have landed before the loop: otherwise the in-order load counter forces every
-    // iteration to wait for its own freshly issued prefetch
+    // From here on the only vector-memory traffic of the loop are the asynchronous copies, which this code counts
+    // itself; the compiler must not be left with pending loads of its own (the Q fragments) that it would wait for
+    // inside the loop.
     wait_vmem_loads();
-    for (int t = 0; t < n_kt; t++) {
-        const __bf16* Ks = smem + (t & 1) * Tile<D>::BUF_ELEMS;
-        const __bf16* Vs = Ks + BN * KS;
-        if (t + 1 < n_kt) load_tile(t + 1);  // global loads in flight while this tile is consumed
-        const int live = L - t * BN;         // keys of this tile inside the history (>= 1)
-#pragma unroll 1
+    if (n_kt > 0) ST::issue(kg, vg, kv_base, p.Hkv, g, L, 0, smem_addr, voff, wave_u, lane);
+    if (AHEAD > 1 && n_kt > 1) {
+        ST::issue(kg, vg, kv_base, p.Hkv, g, L, 1, smem_addr + ST::BYTES, voff, wave_u, lane);
+        wait_vmem_outstanding<ST::COPIES>();
+    } else {
+        wait_vmem_outstanding<0>();
+    }
+    lds_barrier();
+    // Tile t is consumed from stage t % NSTAGE while tile t+AHEAD is fetched into stage (t+AHEAD) % NSTAGE, which was
+    // last read for tile t-1, i.e. before the barrier that every wave has passed.
+    auto tile = [&](int t, auto St) {
+        constexpr int st = decltype(St)::value;
+        if (t + AHEAD < n_kt)
+            ST::issue(kg, vg, kv_base, p.Hkv, g, L, t + AHEAD, smem_addr + ((st + AHEAD) % NSTAGE) * ST::BYTES, voff, wave_u, lane);
+        const __bf16* Ks = (const __bf16*)(smem + st * ST::BYTES);
+        const __bf16* Vs = Ks + ST::TILE;
+        const int live = L - t * BN;  // keys of this tile inside the history (>= 1)
+#pragma unroll
         for (int kb = 0; kb < NKB; kb++) {
             const int n_live = live - kb * 32;
-            if (n_live > 0) subtile(Ks, Vs, kb, n_live);
+            if (n_live > 0) subtile(Ks + kb * 32 * D, Vs + kb * 32 * D, n_live);
         }
-        if (t + 1 < n_kt) store_tile((t + 1) & 1);  // the other buffer: last read before the previous barrier
-        __syncthreads();
+        // tile t+1 must have landed; a tile requested after it may stay in flight
+        if (AHEAD > 1 && t + 2 < n_kt) wait_vmem_outstanding<ST::COPIES>(); else wait_vmem_outstanding<0>();
+        lds_barrier();
+    };
+    for (int t = 0; t < n_kt; t += NSTAGE) {
+        tile(t, std::integral_constant<int, 0>{});
+        if (t + 1 < n_kt) tile(t + 1, std::integral_constant<int, 1>{});
+        if constexpr (NSTAGE > 2) {
+            if (t + 2 < n_kt) tile(t + 2, std::integral_constant<int, 2>{});
+        }
     }
 
     // epilogue: self key of target rows (rule 3), normalisation, stores

@@ -1,16 +1,17 @@
-// LDS tiles fed by asynchronous global -> LDS copies, shared by the bf16 kernels.
+// LDS tiles fed by asynchronous global -> LDS copies: offsets of MFMA operand fragments inside a swizzled tile, and
+// the K/V stage of the row-stationary kernels.
 //
-// A tile is 32 or 64 rows of D bf16, stored unpadded (row pitch D) with the XOR chunk swizzle of hta_mfma.h.
-// One wave-wide copy moves 1 KB: lane i lands at byte 16 i of the 1 KB block, i.e. at chunk position i % (D/8)
-// of tile row (1 KB block index) * (64 / (D/8)) + i / (D/8); it therefore fetches the chunk that the swizzle
-// assigns to that position.
+// A tile is rows of D bf16, stored unpadded (row pitch D) with the XOR chunk swizzle of hta_mfma.h.  One wave-wide
+// copy moves 1 KB: lane i lands at byte 16 i of the 1 KB block, i.e. at chunk position i % (D/8) of tile row
+// (1 KB block index) * (64 / (D/8)) + i / (D/8); it therefore fetches the chunk that the swizzle assigns to that
+// position.
 #pragma once
 #include "hta_mfma.h"
 
 namespace hta {
 
-// element offset, inside a swizzled tile, of the 16-byte fragment (row = lane % 32 (+32 per row block), chunk
-// 2*ks + lane/32) that feeds an MFMA operand whose row index sits on the lane
+// element offset, inside a swizzled tile, of the 16-byte fragment (row = lane % 32, chunk 2*ks + lane/32) that feeds
+// an MFMA operand whose row index sits on the lane.  Adding a multiple of 32 rows leaves the swizzle unchanged.
 template <int D>
 __device__ inline void natural_offsets(int (&off)[D / 16], int lane) {
     const int l32 = lane & 31, hf = lane >> 5;
@@ -31,33 +32,53 @@ __device__ inline void transposed_offsets(int (&lo)[D / 32], int (&hi)[D / 32], 
     }
 }
 
-// K and V tiles of 64 keys each, one stage = [K tile][V tile]
+// K and V tiles of 64 keys each; one stage = [K tile][V tile].  The 2 * COPIES_PER_TILE copies of a stage are dealt
+// to the NW waves of the workgroup, K copies first.
 template <int D, int NW>
 struct KvStage {
     static constexpr int BN = 64;
     static constexpr int TILE = BN * D;                       // elements
-    static constexpr size_t BYTES = (size_t)2 * TILE * 2;     // K + V
+    static constexpr int BYTES = 2 * TILE * 2;                // K + V
     static constexpr int CPR = D / 8;                         // 16-byte chunks per row
     static constexpr int RPC = 64 / CPR;                      // rows per 1 KB copy
     static constexpr int COPIES_PER_TILE = BN / RPC;
     static constexpr int COPIES = 2 * COPIES_PER_TILE / NW;   // per wave and stage
     static_assert((2 * COPIES_PER_TILE) % NW == 0, "copies must split evenly over the waves");
 
-    // Issue this wave's share of the copies of key tile t (keys 64 t .. 64 t + 63 of the history of length L; keys
-    // past the history repeat key L-1: finite data whose weight the caller forces to zero).
-    __device__ static void issue(const __bf16* kg, const __bf16* vg, int64_t kv_base, int Hkv, int g, int L, int t,
-                                 unsigned char* stage, int wave, int lane) {
+    // loop-invariant byte offsets of the chunks this lane fetches, from the first element of (first key of the tile,
+    // kv head g)
+    __device__ static void lane_offsets(uint32_t (&voff)[COPIES], int Hkv, int wave, int lane) {
 #pragma unroll
         for (int jj = 0; jj < COPIES; jj++) {
-            const int c = wave + jj * NW;                 // 0 .. 2*COPIES_PER_TILE-1: K copies first, then V
+            const int j = (wave + jj * NW) % COPIES_PER_TILE;
+            const int trow = j * RPC + lane / CPR;
+            voff[jj] = (uint32_t)((trow * Hkv * D + (((lane % CPR) ^ swizzle<D>(trow)) << 3)) * 2);
+        }
+    }
+
+    // Issue this wave's share of the copies of key tile t (keys 64 t .. 64 t + 63 of a history of length L) into the
+    // stage at LDS byte address `stage`.  Keys past the history repeat key L-1: finite data whose weight the caller
+    // forces to zero.  `wave_u` is the wave index as a uniform value.
+    __device__ static void issue(const __bf16* kg, const __bf16* vg, int64_t kv_base, int Hkv, int g, int L, int t,
+                                 uint32_t stage, const uint32_t (&voff)[COPIES], int wave_u, int lane) {
+        const bool whole = (t + 1) * BN <= L;  // every key exists: no per-lane address arithmetic
+        const int64_t tbase = ((kv_base + (int64_t)t * BN) * Hkv + g) * D;
+#pragma unroll
+        for (int jj = 0; jj < COPIES; jj++) {
+            const int c = wave_u + jj * NW;
             const bool is_v = c >= COPIES_PER_TILE;
             const int j = is_v ? c - COPIES_PER_TILE : c;
-            const int trow = j * RPC + lane / CPR;
-            int key = t * BN + trow;
-            key = key < L ? key : L - 1;
-            const int chunk = (lane % CPR) ^ swizzle<D>(trow);
-            const int64_t off = ((kv_base + key) * Hkv + g) * D + chunk * 8;
-            copy16_global_to_lds((is_v ? vg : kg) + off, stage + (is_v ? (size_t)TILE * 2 : 0) + (size_t)j * 1024);
+            const uint32_t dst = stage + (is_v ? (uint32_t)TILE * 2u : 0u) + (uint32_t)j * 1024u;
+            const __bf16* src = is_v ? vg : kg;
+            if (whole) {
+                copy16_global_to_lds_at(src + tbase, voff[jj], dst);
+            } else {
+                const int trow = j * RPC + lane / CPR;
+                int key = t * BN + trow;
+                key = key < L ? key : L - 1;
+                const int chunk = (lane % CPR) ^ swizzle<D>(trow);
+                copy16_global_to_lds_at(src + ((kv_base + key) * Hkv + g) * D + chunk * 8, dst);
+            }
         }
     }
 };
