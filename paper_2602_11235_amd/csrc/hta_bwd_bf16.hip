@@ -28,6 +28,7 @@
 #include "../../include/mtfm_hta.h"
 #include "hta_common.h"
 #include "hta_mfma.h"
+#include "hta_tiles.h"
 
 namespace hta {
 namespace {
@@ -127,12 +128,15 @@ constexpr int BN = 64;  // keys per LDS tile of the dQ kernel
 
 template <int D, int RB, int NW>
 __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(Params p, int hpb, int n_hc, int tpg) {
-    constexpr int NT = NW * 64;
-    constexpr int KS = D + 8;                      // K/V row pitch (elements)
-    constexpr int BUF_ELEMS = 2 * BN * KS;         // one K tile + one V tile
-    constexpr int CPR = D / 8, NCH = BN * CPR, CH = (NCH + NT - 1) / NT;
+    using ST = KvStage<D, NW>;
     constexpr int NKS = D / 16, NDB = D / 32, NKB = BN / 32;
-    __shared__ __attribute__((aligned(16))) __bf16 smem[2 * BUF_ELEMS];
+    static_assert(ST::BN == BN, "tile height");
+    // NSTAGE stages of [K tile][V tile], filled by asynchronous global -> LDS copies NSTAGE-1 tiles ahead of their use
+    // (two ahead, except for d = 128 where a third stage would cost the second workgroup of the CU).  The compiler
+    // never sees a store into this array (the copies are issued from inline assembly), so it neither orders LDS reads
+    // against them nor drains them; the counted waits and barriers below do that.
+    constexpr int NSTAGE = D <= 64 ? 3 : 2, AHEAD = NSTAGE - 1;
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[NSTAGE * ST::BYTES];
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
     const WorkItem w = decode_work(blockIdx.x, p.batch * p.Hkv * n_hc, p.Hkv * n_hc, tpg);
@@ -152,7 +156,6 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(Params p, int hpb, i
     const __bf16* kg = (const __bf16*)p.k;
     const __bf16* vg = (const __bf16*)p.v;
     const float c2 = p.scale * LOG2E;
-    const int dhalf16 = 16 * ((lane >> 4) & 1);
 
     // per lane: one query row per row block (clamped past the end; never stored then)
     bf16x8 qf[RB][NKS], dof[RB][NKS];
@@ -179,39 +182,20 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(Params p, int hpb, i
             for (int v = 0; v < 16; v++) dQ[rb][db][v] = 0.f;
 
     const int n_kt = (L + BN - 1) / BN;
-    uint4 kreg[CH], vreg[CH];
-    auto load_tile = [&](int t) {
-#pragma unroll
-        for (int i = 0; i < CH; i++) {
-            const int c = tid + i * NT;
-            const int key = t * BN + c / CPR, dc = c % CPR;
-            kreg[i] = make_uint4(0, 0, 0, 0);
-            vreg[i] = make_uint4(0, 0, 0, 0);
-            if (c < NCH && key < L) {  // keys past the history are zero-filled
-                const int64_t off = ((kv_base + key) * p.Hkv + g) * D + dc * 8;
-                kreg[i] = *(const uint4*)(kg + off);
-                vreg[i] = *(const uint4*)(vg + off);
-            }
-        }
-    };
-    auto store_tile = [&](int buf) {
-        __bf16* Kd = smem + buf * BUF_ELEMS;
-        __bf16* Vd = Kd + BN * KS;
-#pragma unroll
-        for (int i = 0; i < CH; i++) {
-            const int c = tid + i * NT;
-            if (c < NCH) {
-                *(uint4*)(Kd + (c / CPR) * KS + (c % CPR) * 8) = kreg[i];
-                *(uint4*)(Vd + (c / CPR) * KS + (c % CPR) * 8) = vreg[i];
-            }
-        }
-    };
-    auto subtile = [&](const __bf16* Ks, const __bf16* Vs, int kb, int n_live) {
+    int nat[NKS], tlo[NDB], thi[NDB];  // per-lane element offsets of the operand fragments inside a swizzled tile
+    natural_offsets<D>(nat, lane);
+    transposed_offsets<D>(tlo, thi, lane);
+    uint32_t voff[ST::COPIES];
+    ST::lane_offsets(voff, p.Hkv, wave, lane);
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const uint32_t smem_addr = lds_address(smem);
+
+    auto subtile = [&](const __bf16* Ks, const __bf16* Vs, int n_live) {  // Ks, Vs: first row of the sub-tile
         floatx16 S[RB], dP[RB];  // S^T, dP^T: [key (registers)][row (lanes)]
 #pragma unroll
         for (int ks = 0; ks < NKS; ks++) {
-            const bf16x8 kf = *(const bf16x8*)(Ks + (kb * 32 + l32) * KS + ks * 16 + 8 * hf);
-            const bf16x8 vf = *(const bf16x8*)(Vs + (kb * 32 + l32) * KS + ks * 16 + 8 * hf);
+            const bf16x8 kf = *(const bf16x8*)(Ks + nat[ks]);
+            const bf16x8 vf = *(const bf16x8*)(Vs + nat[ks]);
 #pragma unroll
             for (int rb = 0; rb < RB; rb++) {
                 if (ks == 0) {
@@ -246,30 +230,48 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(Params p, int hpb, i
         for (int db = 0; db < NDB; db++)
 #pragma unroll
             for (int s2 = 0; s2 < 2; s2++) {
-                const bf16x8 ktf = lds_read_tr_8(Ks, KS, kb * 32 + 16 * s2 + 4 * hf, db * 32 + dhalf16, lane);
+                const bf16x8 ktf = lds_read_tr_pair(Ks + 16 * s2 * D + tlo[db], Ks + 16 * s2 * D + thi[db]);
 #pragma unroll
                 for (int rb = 0; rb < RB; rb++) dQ[rb][db] = mfma32(ktf, dsb[rb][s2], dQ[rb][db]);
             }
     };
 
-    if (n_kt > 0) {
-        load_tile(0);
-        store_tile(0);
-        __syncthreads();
+    // From here on the only vector-memory traffic of the loop are the asynchronous copies, which this code counts
+    // itself; the compiler must not be left with pending loads of its own (Q, dO, lse, delta) that it would wait for
+    // inside the loop.
+    wait_vmem_loads();
+    if (n_kt > 0) ST::issue(kg, vg, kv_base, p.Hkv, g, L, 0, smem_addr, voff, wave_u, lane);
+    if (AHEAD > 1 && n_kt > 1) {
+        ST::issue(kg, vg, kv_base, p.Hkv, g, L, 1, smem_addr + ST::BYTES, voff, wave_u, lane);
+        wait_vmem_outstanding<ST::COPIES>();
+    } else {
+        wait_vmem_outstanding<0>();
     }
-    wait_vmem_loads();  // Q, dO, lse, delta have landed: the loop's load counter only tracks its own prefetch
-    for (int t = 0; t < n_kt; t++) {
-        const __bf16* Ks = smem + (t & 1) * BUF_ELEMS;
-        const __bf16* Vs = Ks + BN * KS;
-        if (t + 1 < n_kt) load_tile(t + 1);
-        const int live = L - t * BN;
-#pragma unroll 1
+    lds_barrier();
+    // Tile t is consumed from stage t % NSTAGE while tile t+AHEAD is fetched into stage (t+AHEAD) % NSTAGE, which was
+    // last read for tile t-1, i.e. before the barrier that every wave has passed.
+    auto tile = [&](int t, auto St) {
+        constexpr int st = decltype(St)::value;
+        if (t + AHEAD < n_kt)
+            ST::issue(kg, vg, kv_base, p.Hkv, g, L, t + AHEAD, smem_addr + ((st + AHEAD) % NSTAGE) * ST::BYTES, voff, wave_u, lane);
+        const __bf16* Ks = (const __bf16*)(smem + st * ST::BYTES);
+        const __bf16* Vs = Ks + ST::TILE;
+        const int live = L - t * BN;  // keys of this tile inside the history (>= 1)
+#pragma unroll
         for (int kb = 0; kb < NKB; kb++) {
             const int n_live = live - kb * 32;
-            if (n_live > 0) subtile(Ks, Vs, kb, n_live);
+            if (n_live > 0) subtile(Ks + kb * 32 * D, Vs + kb * 32 * D, n_live);
         }
-        if (t + 1 < n_kt) store_tile((t + 1) & 1);
-        __syncthreads();
+        // tile t+1 must have landed; a tile requested after it may stay in flight
+        if (AHEAD > 1 && t + 2 < n_kt) wait_vmem_outstanding<ST::COPIES>(); else wait_vmem_outstanding<0>();
+        lds_barrier();
+    };
+    for (int t = 0; t < n_kt; t += NSTAGE) {
+        tile(t, std::integral_constant<int, 0>{});
+        if (t + 1 < n_kt) tile(t + 1, std::integral_constant<int, 1>{});
+        if constexpr (NSTAGE > 2) {
+            if (t + 2 < n_kt) tile(t + 2, std::integral_constant<int, 2>{});
+        }
     }
 
     // epilogue: self key of target rows (rule 3), scale, store
