@@ -149,7 +149,7 @@ def main() -> int:
         step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    kinds = {"fwd": hta.KERNEL_FWD, "bwd_pre": hta.KERNEL_BWD_PRE, "bwd_dq": hta.KERNEL_BWD_DQ,
+    kinds = {"fwd": hta.KERNEL_FWD, "bwd_self": hta.KERNEL_BWD_SELF, "bwd_dq": hta.KERNEL_BWD_DQ,
              "bwd_dkdv": hta.KERNEL_BWD_DKDV}
     kernel_ms = {name: hta.mtfm_hta_timing_read(kind) for name, kind in kinds.items()}
     hta.mtfm_hta_timing_enable(0)

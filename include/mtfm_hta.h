@@ -141,7 +141,7 @@ MTFM_HTA_API int mtfm_hta_validate_host(const int32_t* q_offsets, const int32_t*
  * Process-wide state; not meant to be toggled while another thread is inside a call.
  */
 enum { MTFM_HTA_KERNEL_FWD = 0,      /* forward attention kernel */
-       MTFM_HTA_KERNEL_BWD_PRE = 1,  /* delta = <dout, out> per row, dk/dv of the target tokens' own keys */
+       MTFM_HTA_KERNEL_BWD_SELF = 1, /* dk/dv of the target tokens' own keys */
        MTFM_HTA_KERNEL_BWD_DQ = 2,   /* dq (row-stationary pass; the whole backward of the fp32 path) */
        MTFM_HTA_KERNEL_BWD_DKDV = 3, /* dk, dv of the history keys (key-stationary pass) */
        MTFM_HTA_N_KERNELS = 4 };

@@ -6,14 +6,14 @@
 //   dV = P^T dO,  dK = scale dS^T Q  (both summed over the query heads of the kv group),  dQ = scale dS K
 //
 // Three kernels, no atomics, no float32 staging of any gradient:
-//   1. bwd_pre:  delta for every (row, head), and the self-key terms of target rows' keys (rule 3: a
-//      target key is seen by its own row only, so its dk/dv come from that row alone and are written
-//      here, final, in bf16).
+//   1. bwd_self: the self-key terms of target rows' keys (rule 3: a target key is seen by its own row
+//      only, so its dk/dv come from that row alone and are written here, final, in bf16).
 //   2. bwd_dq:   row-stationary, the forward kernel's decomposition: a wave keeps query rows (Q, dO, dQ) in
 //      registers and streams the history K/V tiles through LDS.  S^T = K Q^T and dP^T = V dO^T have
 //      the query row on the lane, so lse and delta are one register each and dS^T in accumulator layout
 //      is directly the k-operand of dQ^T = K^T dS^T.  The self key of a target row is one extra term
-//      in the epilogue.  dq is written once.
+//      in the epilogue.  dq is written once.  delta_i = <dO_i, O_i> is formed here, from the dO fragments
+//      the wave holds anyway, and left (negated, with -lse/scale) in the workspace for the third kernel.
 //   3. bwd_dkdv: key-stationary: a wave owns 32 history keys (K, V fragments and the dK, dV accumulators
 //      stay in registers for the whole kernel), the workgroup streams (head, 32-row block) tiles of Q
 //      and dO through LDS, shared by its waves.  S = Q K^T and dP = dO V^T have the key on the lane, so
@@ -38,89 +38,69 @@ __device__ inline float group_sum(float x, int width) {  // sum over aligned gro
     return x;
 }
 
-// ---------------------------------------------------------------------------------------- pre
-// One group of D/8 lanes per (query row, kv head); the group walks the r query heads of the kv head.
+// ---------------------------------------------------------------------------------------- self keys
+// One group of D/8 lanes per (target token, kv head); the group walks the r query heads of the kv head.
 template <int D>
-__global__ __launch_bounds__(256) void bwd_pre_kernel(Params p) {
+__global__ __launch_bounds__(256) void bwd_self_kernel(Params p) {
     constexpr int LPR = D / 8;           // lanes per item, 8 elements (16 bytes) each
     constexpr int IPB = 256 / LPR;       // items per block
     const int b = blockIdx.z;  // bandwidth-bound pass: user order does not matter
     const int L = p.hist_len[b], T = p.n_targets[b];
-    const int n_rows = p.layer == 0 ? L + T : T;
     const int r = p.Hq / p.Hkv;
-    const int item = blockIdx.x * IPB + threadIdx.x / LPR;  // (row, g) flattened, g fastest
+    const int item = blockIdx.x * IPB + threadIdx.x / LPR;  // (target, g) flattened, g fastest
     const int sub = threadIdx.x % LPR;
-    const int row = item / p.Hkv, g = item % p.Hkv;
-    // behind the -lse/scale array: what the S accumulators of rows that do not exist start from in the dK/dV pass
-    if (blockIdx.x == 0 && blockIdx.z == 0 && threadIdx.x == 0) p.neg_lse_s[(int64_t)p.Hq * p.total_q] = -1e30f;
-    if (row >= n_rows) return;  // whole lane groups leave together; group_sum only talks inside a group
-    const int64_t q_row = (int64_t)p.q_off[b] + row;
-    const int tok = (p.layer == 0 ? 0 : L) + row;
-    const bool is_target = tok >= L;
+    const int t = item / p.Hkv, g = item % p.Hkv;
+    if (t >= T) return;  // whole lane groups leave together; group_sum only talks inside a group
+    const int64_t q_row = (int64_t)p.q_off[b] + (p.layer == 0 ? L + t : t);
     const __bf16* qg = (const __bf16*)p.q;
     const __bf16* dog = (const __bf16*)p.dout;
     const __bf16* og = (const __bf16*)p.out;
+    const int64_t kv_off = (((int64_t)p.kv_off[b] + L + t) * p.Hkv + g) * D + sub * 8;
+    const bf16x8 kk = *(const bf16x8*)((const __bf16*)p.k + kv_off);
+    const bf16x8 vv = *(const bf16x8*)((const __bf16*)p.v + kv_off);
     float kself[8], vself[8], dk_t[8], dv_t[8];
-    int64_t kv_off = 0;
-    if (is_target) {
-        kv_off = (((int64_t)p.kv_off[b] + tok) * p.Hkv + g) * D + sub * 8;
-        const bf16x8 kk = *(const bf16x8*)((const __bf16*)p.k + kv_off);
-        const bf16x8 vv = *(const bf16x8*)((const __bf16*)p.v + kv_off);
 #pragma unroll
-        for (int j = 0; j < 8; j++) {
-            kself[j] = (float)kk[j];
-            vself[j] = (float)vv[j];
-            dk_t[j] = 0.f;
-            dv_t[j] = 0.f;
-        }
+    for (int j = 0; j < 8; j++) {
+        kself[j] = (float)kk[j];
+        vself[j] = (float)vv[j];
+        dk_t[j] = 0.f;
+        dv_t[j] = 0.f;
     }
     for (int hh = 0; hh < r; hh++) {
         const int h = g * r + hh;
         const int64_t off = (q_row * p.Hq + h) * D + sub * 8;
         const bf16x8 dov = *(const bf16x8*)(dog + off);
         const bf16x8 ov = *(const bf16x8*)(og + off);
-        float dof[8], part = 0.f;
+        const bf16x8 qv = *(const bf16x8*)(qg + off);
+        float dof[8], qf[8], part = 0.f, sp = 0.f, dpp = 0.f;
 #pragma unroll
         for (int j = 0; j < 8; j++) {
             dof[j] = (float)dov[j];
+            qf[j] = (float)qv[j];
             part = fmaf(dof[j], (float)ov[j], part);
+            sp = fmaf(qf[j], kself[j], sp);
+            dpp = fmaf(dof[j], vself[j], dpp);
         }
         const float delta = group_sum(part, LPR);
         const float lse = p.lse[(int64_t)h * p.total_q + q_row];
-        if (sub == 0) {
-            p.neg_delta[(int64_t)h * p.total_q + q_row] = -delta;
-            p.neg_lse_s[(int64_t)h * p.total_q + q_row] = -lse / p.scale;
-        }
-        if (is_target) {
-            const bf16x8 qv = *(const bf16x8*)(qg + off);
-            float qf[8], sp = 0.f, dpp = 0.f;
-#pragma unroll
-            for (int j = 0; j < 8; j++) {
-                qf[j] = (float)qv[j];
-                sp = fmaf(qf[j], kself[j], sp);
-                dpp = fmaf(dof[j], vself[j], dpp);
-            }
-            const float s = group_sum(sp, LPR) * p.scale;
-            const float dp = group_sum(dpp, LPR);
-            const float pw = __expf(s - lse);
-            const float ds = pw * (dp - delta) * p.scale;
-#pragma unroll
-            for (int j = 0; j < 8; j++) {
-                dk_t[j] = fmaf(ds, qf[j], dk_t[j]);
-                dv_t[j] = fmaf(pw, dof[j], dv_t[j]);
-            }
-        }
-    }
-    if (is_target) {
-        bf16x8 dk8, dv8;
+        const float sc = group_sum(sp, LPR) * p.scale;
+        const float dp = group_sum(dpp, LPR);
+        const float pw = __expf(sc - lse);
+        const float ds = pw * (dp - delta) * p.scale;
 #pragma unroll
         for (int j = 0; j < 8; j++) {
-            dk8[j] = (__bf16)dk_t[j];
-            dv8[j] = (__bf16)dv_t[j];
+            dk_t[j] = fmaf(ds, qf[j], dk_t[j]);
+            dv_t[j] = fmaf(pw, dof[j], dv_t[j]);
         }
-        *(bf16x8*)((__bf16*)p.dk + kv_off) = dk8;
-        *(bf16x8*)((__bf16*)p.dv + kv_off) = dv8;
     }
+    bf16x8 dk8, dv8;
+#pragma unroll
+    for (int j = 0; j < 8; j++) {
+        dk8[j] = (__bf16)dk_t[j];
+        dv8[j] = (__bf16)dv_t[j];
+    }
+    *(bf16x8*)((__bf16*)p.dk + kv_off) = dk8;
+    *(bf16x8*)((__bf16*)p.dv + kv_off) = dv8;
 }
 
 // ---------------------------------------------------------------------------------------- dQ
@@ -139,6 +119,8 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(Params p, int hpb, i
     __shared__ __attribute__((aligned(1024))) unsigned char smem[NSTAGE * ST::BYTES];
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
+    // behind the -lse/scale array: what the S accumulators of rows that do not exist start from in the dK/dV pass
+    if (blockIdx.x == 0 && tid == 0) p.neg_lse_s[(int64_t)p.Hq * p.total_q] = -1e30f;
     const WorkItem w = decode_work(blockIdx.x, p.batch * p.Hkv * n_hc, p.Hkv * n_hc, tpg);
     if (!w.valid) return;
     const int b = scheduled_user(p, w.user_slot);
@@ -163,15 +145,26 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(Params p, int hpb, i
 #pragma unroll
     for (int rb = 0; rb < RB; rb++) {
         int row = wrow0 + rb * 32 + l32;
-        row = row < n_rows ? row : n_rows - 1;
+        const bool row_live = row < n_rows;
+        row = row_live ? row : n_rows - 1;
         const int64_t off = ((q_base + row) * p.Hq + h) * D + 8 * hf;
+        float part = 0.f;  // this lane's half of delta = <dO, O>
 #pragma unroll
         for (int ks = 0; ks < NKS; ks++) {
             qf[rb][ks] = *(const bf16x8*)((const __bf16*)p.q + off + ks * 16);
             dof[rb][ks] = *(const bf16x8*)((const __bf16*)p.dout + off + ks * 16);
+            part = dot_bf16x8(part, dof[rb][ks], *(const bf16x8*)((const __bf16*)p.out + off + ks * 16));
         }
-        lse2[rb] = p.lse[(int64_t)h * p.total_q + q_base + row] * LOG2E;
-        dl[rb] = p.neg_delta[(int64_t)h * p.total_q + q_base + row];  // -delta
+        const int64_t stat = (int64_t)h * p.total_q + q_base + row;
+        const float lse = p.lse[stat];
+        const float delta = part + other_half(part);
+        lse2[rb] = lse * LOG2E;
+        dl[rb] = -delta;
+        // every (row, head) belongs to exactly one wave of this kernel: it leaves the row statistics for the dK/dV pass
+        if (row_live && hf == 0) {
+            p.neg_delta[stat] = -delta;
+            p.neg_lse_s[stat] = -lse / p.scale;
+        }
     }
     floatx16 dQ[RB][NDB];  // dQ^T: [d (registers)][row (lanes)]
 #pragma unroll
@@ -703,13 +696,12 @@ hipError_t launch_dkdv(const Params& p, hipStream_t s) {
 }
 
 template <int D>
-hipError_t launch_pre(const Params& p, hipStream_t s) {
-    const int64_t rows = max_query_rows(p);
-    if (rows <= 0) return hipSuccess;
+hipError_t launch_self(const Params& p, hipStream_t s) {
+    if (p.max_targets <= 0) return hipSuccess;
     constexpr int IPB = 256 / (D / 8);
-    const int64_t items = rows * p.Hkv;
+    const int64_t items = (int64_t)p.max_targets * p.Hkv;
     dim3 grid((unsigned)((items + IPB - 1) / IPB), 1, (unsigned)p.batch);
-    hipLaunchKernelGGL(bwd_pre_kernel<D>, grid, dim3(256), 0, s, p);
+    hipLaunchKernelGGL(bwd_self_kernel<D>, grid, dim3(256), 0, s, p);
     return hipGetLastError();
 }
 
@@ -717,14 +709,14 @@ hipError_t launch_pre(const Params& p, hipStream_t s) {
 
 hipError_t launch_bwd_bf16(const Params& p, hipStream_t s) {
     hipError_t e;
-    timing_begin(MTFM_HTA_KERNEL_BWD_PRE, s);
+    timing_begin(MTFM_HTA_KERNEL_BWD_SELF, s);
     switch (p.d) {
-        case 32: e = launch_pre<32>(p, s); break;
-        case 64: e = launch_pre<64>(p, s); break;
-        case 128: e = launch_pre<128>(p, s); break;
+        case 32: e = launch_self<32>(p, s); break;
+        case 64: e = launch_self<64>(p, s); break;
+        case 128: e = launch_self<128>(p, s); break;
         default: e = hipErrorInvalidValue;
     }
-    timing_end(MTFM_HTA_KERNEL_BWD_PRE, s);
+    timing_end(MTFM_HTA_KERNEL_BWD_SELF, s);
     if (e != hipSuccess) return e;
     const bool wide = ((p.Hq / p.Hkv) % 8) == 0;
     timing_begin(MTFM_HTA_KERNEL_BWD_DQ, s);

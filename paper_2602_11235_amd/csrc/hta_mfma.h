@@ -68,6 +68,15 @@ __device__ inline void add_bf16x8(float& acc0, float& acc1, bf16x8 x) {
     acc1 = __builtin_amdgcn_fdot2_f32_bf16(d, one, acc1, false);
 }
 
+// acc + <x, y> for eight packed bf16 pairs: products are exact in float32, sums are float32
+__device__ inline float dot_bf16x8(float acc, bf16x8 x, bf16x8 y) {
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(x, x, 0, 1), __builtin_shufflevector(y, y, 0, 1), acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(x, x, 2, 3), __builtin_shufflevector(y, y, 2, 3), acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(x, x, 4, 5), __builtin_shufflevector(y, y, 4, 5), acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(x, x, 6, 7), __builtin_shufflevector(y, y, 6, 7), acc, false);
+    return acc;
+}
+
 // wait until every outstanding vector-memory load of this wave has landed
 __device__ inline void wait_vmem_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 

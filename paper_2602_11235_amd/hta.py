@@ -19,7 +19,7 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_LAUNCH = 0, -1, -2, -3,
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmtfm_hta.so")
 EXPORTS = ("mtfm_hta_workspace_bytes", "mtfm_hta_fwd", "mtfm_hta_bwd", "mtfm_hta_validate_host",
            "mtfm_hta_last_error", "mtfm_hta_version", "mtfm_hta_timing_enable", "mtfm_hta_timing_read")
-KERNEL_FWD, KERNEL_BWD_PRE, KERNEL_BWD_DQ, KERNEL_BWD_DKDV = 0, 1, 2, 3
+KERNEL_FWD, KERNEL_BWD_SELF, KERNEL_BWD_DQ, KERNEL_BWD_DKDV = 0, 1, 2, 3
 
 _lib = None
 
