@@ -10,19 +10,22 @@
  *   target attention layer  A_T^(h) = phi2(Q_T^(h) K^(g)T (.) M_T) V^(g)     queries = T-tokens only,
  *                           M_T = the T-token rows of M, K/V from all tokens
  *   g = ceil(h / r) for 1-based h, r = H / G (grouped-query attention): with 0-based heads, g = h / r.
- *   Dynamic mask M, rules 1 and 3: history tokens are visible to every token; a target token is
- *   visible only to itself.  (Rule 2, the timestamp rule for real-time tokens, is not part of
- *   this path: a user's sample here is history tokens followed by target tokens.)
+ *   Dynamic mask M: rule 1, history tokens are visible to every token; rule 2, a real-time token is
+ *   visible only to tokens with later timestamps; rule 3, a target token is visible only to itself.
+ *   The functions without the _rt suffix are the case without real-time tokens (rules 1 and 3).
  *
  * Readings where the paper is silent (kept identical in the GPU library):
  *   - phi2 is a row softmax over the visible keys; masked keys are excluded (weight exactly 0).
  *   - "X visible to Y" means query Y may attend to key X; rows of M are queries.
  *   - logits are scaled by an explicit softmax_scale argument.
  *   - lse is the natural-log logsumexp of the scaled visible logits.
+ *   - rule 2: "later" is strict (key timestamp < query timestamp), for every kind of query token; in
+ *     addition a real-time token sees itself, like a target token does, so that no row is empty.
  *
  * Layout: q/out/dout/dq are [total_q][Hq][d]; k/v/dk/dv are [total_kv][Hkv][d]; lse is [Hq][total_q].
- * Per user b the K/V rows are L_b history tokens then T_b target tokens, starting at kv_start[b].
- * Query rows start at q_start[b]: N_b = L_b + T_b rows in a full layer, T_b rows in a target layer.
+ * Per user b the K/V rows are L_b history tokens, then R_b real-time tokens, then T_b target tokens
+ * (X = (H; R; T), Section 3.2.1), starting at kv_start[b]; ts[] holds one timestamp per K/V row.
+ * Query rows start at q_start[b]: N_b = L_b + R_b + T_b rows in a full layer, T_b rows in a target layer.
  */
 #include <math.h>
 #include <stdint.h>
@@ -32,16 +35,39 @@
 #include <omp.h>
 #endif
 
-enum { TOKEN_HISTORY = 0, TOKEN_TARGET = 1 };
+enum { TOKEN_HISTORY = 0, TOKEN_REALTIME = 1, TOKEN_TARGET = 2 };
 enum { LAYER_FULL = 0, LAYER_TARGET = 1 };
 
+/* one user's sample: segment lengths and the timestamps of its tokens (NULL when it has no real-time tokens) */
+typedef struct {
+    int64_t hist_len, rt_len, n_targets;
+    const int32_t* ts;
+} sample_t;
+
 /* type of token number `tok` (0-based within the user's sample) */
-static int token_type(int64_t tok, int64_t hist_len) { return tok < hist_len ? TOKEN_HISTORY : TOKEN_TARGET; }
+static int token_type(int64_t tok, const sample_t* u) {
+    if (tok < u->hist_len) return TOKEN_HISTORY;
+    if (tok < u->hist_len + u->rt_len) return TOKEN_REALTIME;
+    return TOKEN_TARGET;
+}
 
 /* dynamic mask entry M[query token][key token] */
-static int visible(int64_t query_tok, int64_t key_tok, int64_t hist_len) {
-    if (token_type(key_tok, hist_len) == TOKEN_HISTORY) return 1; /* rule 1 */
-    return key_tok == query_tok;                                   /* rule 3 */
+static int visible(int64_t query_tok, int64_t key_tok, const sample_t* u) {
+    switch (token_type(key_tok, u)) {
+        case TOKEN_HISTORY: return 1;                                                               /* rule 1 */
+        case TOKEN_REALTIME: return u->ts[key_tok] < u->ts[query_tok] || key_tok == query_tok;      /* rule 2 */
+        default: return key_tok == query_tok;                                                       /* rule 3 */
+    }
+}
+
+static sample_t sample_of(int b, const int32_t* kv_start, const int32_t* hist_len, const int32_t* rt_len,
+                          const int32_t* n_targets, const int32_t* ts) {
+    sample_t u;
+    u.hist_len = hist_len[b];
+    u.rt_len = rt_len ? rt_len[b] : 0;
+    u.n_targets = n_targets[b];
+    u.ts = ts ? ts + kv_start[b] : NULL;
+    return u;
 }
 
 int hta_oracle_num_threads(void) {
@@ -52,20 +78,22 @@ int hta_oracle_num_threads(void) {
 #endif
 }
 
-/* Forward.  Returns 0, or -1 on bad scalar arguments. */
-int hta_oracle_fwd(const double* q, const double* k, const double* v, double* out, double* lse,
-                   const int32_t* q_start, const int32_t* kv_start, const int32_t* hist_len,
-                   const int32_t* n_targets, int32_t batch, int64_t total_q, int32_t Hq, int32_t Hkv,
-                   int32_t d, double scale, int32_t layer) {
+/* Forward.  rt_len and ts may both be NULL (no real-time tokens).  Returns 0, or -1 on bad scalar arguments. */
+int hta_oracle_fwd_rt(const double* q, const double* k, const double* v, double* out, double* lse,
+                      const int32_t* q_start, const int32_t* kv_start, const int32_t* hist_len,
+                      const int32_t* rt_len, const int32_t* n_targets, const int32_t* ts, int32_t batch,
+                      int64_t total_q, int32_t Hq, int32_t Hkv, int32_t d, double scale, int32_t layer) {
     if (Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0 || d <= 0 || batch < 0) return -1;
     if (layer != LAYER_FULL && layer != LAYER_TARGET) return -1;
+    if (rt_len && !ts) return -1;
     const int r = Hq / Hkv;
 #pragma omp parallel for collapse(2) schedule(dynamic, 1)
     for (int b = 0; b < batch; b++) {
         for (int h = 0; h < Hq; h++) {
             const int g = h / r;
-            const int64_t L = hist_len[b], T = n_targets[b], N = L + T;
-            const int64_t first_tok = (layer == LAYER_FULL) ? 0 : L; /* token of query row 0 */
+            const sample_t u = sample_of(b, kv_start, hist_len, rt_len, n_targets, ts);
+            const int64_t N = u.hist_len + u.rt_len + u.n_targets;
+            const int64_t first_tok = (layer == LAYER_FULL) ? 0 : u.hist_len + u.rt_len; /* token of query row 0 */
             const int64_t n_rows = N - first_tok;
             double* s = (double*)malloc((size_t)(N > 0 ? N : 1) * sizeof(double));
             for (int64_t row = 0; row < n_rows; row++) {
@@ -73,7 +101,7 @@ int hta_oracle_fwd(const double* q, const double* k, const double* v, double* ou
                 const double* qi = q + ((int64_t)(q_start[b] + row) * Hq + h) * d;
                 double smax = -INFINITY;
                 for (int64_t j = 0; j < N; j++) {
-                    if (!visible(i, j, L)) continue;
+                    if (!visible(i, j, &u)) continue;
                     const double* kj = k + ((int64_t)(kv_start[b] + j) * Hkv + g) * d;
                     double dot = 0.0;
                     for (int c = 0; c < d; c++) dot += qi[c] * kj[c];
@@ -82,12 +110,12 @@ int hta_oracle_fwd(const double* q, const double* k, const double* v, double* ou
                 }
                 double denom = 0.0;
                 for (int64_t j = 0; j < N; j++)
-                    if (visible(i, j, L)) denom += exp(s[j] - smax);
+                    if (visible(i, j, &u)) denom += exp(s[j] - smax);
                 const double lse_i = smax + log(denom);
                 double* oi = out + ((int64_t)(q_start[b] + row) * Hq + h) * d;
                 for (int c = 0; c < d; c++) oi[c] = 0.0;
                 for (int64_t j = 0; j < N; j++) {
-                    if (!visible(i, j, L)) continue;
+                    if (!visible(i, j, &u)) continue;
                     const double p = exp(s[j] - lse_i);
                     const double* vj = v + ((int64_t)(kv_start[b] + j) * Hkv + g) * d;
                     for (int c = 0; c < d; c++) oi[c] += p * vj[c];
@@ -108,19 +136,21 @@ int hta_oracle_fwd(const double* q, const double* k, const double* v, double* ou
  *   dv_j  = sum_{h in g} sum_i p_ij dout_i
  * dq, dk, dv are fully overwritten.  `out` and `lse` must come from hta_oracle_fwd on the same inputs.
  */
-int hta_oracle_bwd(const double* dout, const double* q, const double* k, const double* v,
-                   const double* out, const double* lse, double* dq, double* dk, double* dv,
-                   const int32_t* q_start, const int32_t* kv_start, const int32_t* hist_len,
-                   const int32_t* n_targets, int32_t batch, int64_t total_q, int32_t Hq, int32_t Hkv,
-                   int32_t d, double scale, int32_t layer) {
+int hta_oracle_bwd_rt(const double* dout, const double* q, const double* k, const double* v,
+                      const double* out, const double* lse, double* dq, double* dk, double* dv,
+                      const int32_t* q_start, const int32_t* kv_start, const int32_t* hist_len,
+                      const int32_t* rt_len, const int32_t* n_targets, const int32_t* ts, int32_t batch,
+                      int64_t total_q, int32_t Hq, int32_t Hkv, int32_t d, double scale, int32_t layer) {
     if (Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0 || d <= 0 || batch < 0) return -1;
     if (layer != LAYER_FULL && layer != LAYER_TARGET) return -1;
+    if (rt_len && !ts) return -1;
     const int r = Hq / Hkv;
 #pragma omp parallel for collapse(2) schedule(dynamic, 1)
     for (int b = 0; b < batch; b++) {
         for (int g = 0; g < Hkv; g++) { /* one thread owns all of dk/dv[b, :, g, :] */
-            const int64_t L = hist_len[b], T = n_targets[b], N = L + T;
-            const int64_t first_tok = (layer == LAYER_FULL) ? 0 : L;
+            const sample_t u = sample_of(b, kv_start, hist_len, rt_len, n_targets, ts);
+            const int64_t N = u.hist_len + u.rt_len + u.n_targets;
+            const int64_t first_tok = (layer == LAYER_FULL) ? 0 : u.hist_len + u.rt_len;
             const int64_t n_rows = N - first_tok;
             for (int64_t j = 0; j < N; j++) {
                 double* dkj = dk + ((int64_t)(kv_start[b] + j) * Hkv + g) * d;
@@ -140,7 +170,7 @@ int hta_oracle_bwd(const double* dout, const double* q, const double* k, const d
                     for (int c = 0; c < d; c++) delta += doi[c] * oi[c];
                     for (int c = 0; c < d; c++) dqi[c] = 0.0;
                     for (int64_t j = 0; j < N; j++) {
-                        if (!visible(i, j, L)) continue;
+                        if (!visible(i, j, &u)) continue;
                         const int64_t kvrow = (int64_t)(kv_start[b] + j) * Hkv + g;
                         const double* kj = k + kvrow * d;
                         const double* vj = v + kvrow * d;
@@ -165,13 +195,19 @@ int hta_oracle_bwd(const double* dout, const double* q, const double* k, const d
 
 /* Attention probabilities of one (user, head) as a dense [n_rows][N] matrix (0 where masked):
  * lets tests check that rows sum to one and inspect which pairs carry weight. */
-int hta_oracle_probs(const double* q, const double* k, double* probs, int32_t q_start, int32_t kv_start,
-                     int32_t hist_len, int32_t n_targets, int32_t head, int32_t Hq, int32_t Hkv, int32_t d,
-                     double scale, int32_t layer) {
+int hta_oracle_probs_rt(const double* q, const double* k, double* probs, int32_t q_start, int32_t kv_start,
+                        int32_t hist_len, int32_t rt_len, int32_t n_targets, const int32_t* ts, int32_t head,
+                        int32_t Hq, int32_t Hkv, int32_t d, double scale, int32_t layer) {
     if (Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0 || d <= 0 || head < 0 || head >= Hq) return -1;
+    if (rt_len > 0 && !ts) return -1;
     const int r = Hq / Hkv, g = head / r;
-    const int64_t L = hist_len, N = (int64_t)hist_len + n_targets;
-    const int64_t first_tok = (layer == LAYER_FULL) ? 0 : L;
+    sample_t u;
+    u.hist_len = hist_len;
+    u.rt_len = rt_len;
+    u.n_targets = n_targets;
+    u.ts = ts ? ts + kv_start : NULL;
+    const int64_t N = (int64_t)hist_len + rt_len + n_targets;
+    const int64_t first_tok = (layer == LAYER_FULL) ? 0 : (int64_t)hist_len + rt_len;
     for (int64_t row = 0; row < N - first_tok; row++) {
         const int64_t i = first_tok + row;
         const double* qi = q + ((int64_t)(q_start + row) * Hq + head) * d;
@@ -179,7 +215,7 @@ int hta_oracle_probs(const double* q, const double* k, double* probs, int32_t q_
         double smax = -INFINITY;
         for (int64_t j = 0; j < N; j++) {
             pr[j] = 0.0;
-            if (!visible(i, j, L)) continue;
+            if (!visible(i, j, &u)) continue;
             const double* kj = k + ((int64_t)(kv_start + j) * Hkv + g) * d;
             double dot = 0.0;
             for (int c = 0; c < d; c++) dot += qi[c] * kj[c];
@@ -188,8 +224,33 @@ int hta_oracle_probs(const double* q, const double* k, double* probs, int32_t q_
         }
         double denom = 0.0;
         for (int64_t j = 0; j < N; j++)
-            if (visible(i, j, L)) denom += exp(pr[j] - smax);
-        for (int64_t j = 0; j < N; j++) pr[j] = visible(i, j, L) ? exp(pr[j] - smax) / denom : 0.0;
+            if (visible(i, j, &u)) denom += exp(pr[j] - smax);
+        for (int64_t j = 0; j < N; j++) pr[j] = visible(i, j, &u) ? exp(pr[j] - smax) / denom : 0.0;
     }
     return 0;
+}
+
+/* The case without real-time tokens: every sample is history tokens followed by target tokens (rules 1 and 3). */
+int hta_oracle_fwd(const double* q, const double* k, const double* v, double* out, double* lse,
+                   const int32_t* q_start, const int32_t* kv_start, const int32_t* hist_len,
+                   const int32_t* n_targets, int32_t batch, int64_t total_q, int32_t Hq, int32_t Hkv,
+                   int32_t d, double scale, int32_t layer) {
+    return hta_oracle_fwd_rt(q, k, v, out, lse, q_start, kv_start, hist_len, NULL, n_targets, NULL, batch, total_q, Hq,
+                             Hkv, d, scale, layer);
+}
+
+int hta_oracle_bwd(const double* dout, const double* q, const double* k, const double* v,
+                   const double* out, const double* lse, double* dq, double* dk, double* dv,
+                   const int32_t* q_start, const int32_t* kv_start, const int32_t* hist_len,
+                   const int32_t* n_targets, int32_t batch, int64_t total_q, int32_t Hq, int32_t Hkv,
+                   int32_t d, double scale, int32_t layer) {
+    return hta_oracle_bwd_rt(dout, q, k, v, out, lse, dq, dk, dv, q_start, kv_start, hist_len, NULL, n_targets, NULL,
+                             batch, total_q, Hq, Hkv, d, scale, layer);
+}
+
+int hta_oracle_probs(const double* q, const double* k, double* probs, int32_t q_start, int32_t kv_start,
+                     int32_t hist_len, int32_t n_targets, int32_t head, int32_t Hq, int32_t Hkv, int32_t d,
+                     double scale, int32_t layer) {
+    return hta_oracle_probs_rt(q, k, probs, q_start, kv_start, hist_len, 0, n_targets, NULL, head, Hq, Hkv, d, scale,
+                               layer);
 }

@@ -118,6 +118,16 @@ class Config:
     std: float          # q, k, v ~ std * N(0, 1)
     seed: int
     dout_std: float = 1.0
+    rt: Optional[tuple] = None   # length spec of the real-time segment between history and targets, or None
+
+
+# Timestamp windows of the three token kinds when a workload has real-time tokens (integers, drawn uniformly; history
+# and real-time tokens are then sorted by time inside their segment, as Section 3.2.1 prescribes).  The windows
+# overlap and are narrow on purpose: real-time tokens before and after an exposure, ties, history tokens later than
+# some real-time tokens all occur.
+TS_WINDOW_HIST = (0, 1000)
+TS_WINDOW_RT = (900, 1100)
+TS_WINDOW_TGT = (880, 1120)
 
 
 CONFIGS: Dict[str, Config] = {
@@ -128,10 +138,17 @@ CONFIGS: Dict[str, Config] = {
     "C3_1024": Config("C3_1024", LAYER_FULL, 256, ("fixed", 1024), ("fixed", 64), 8, 2, 64, "bf16", 0.3, 2),
     "C4": Config("C4", LAYER_TARGET, 512, ("fixed", 2048), ("fixed", 128), 16, 4, 64, "bf16", 0.3, 3),
     "C5": Config("C5", LAYER_FULL, 128, ("pareto", 750.0, 8192), ("uniform", 16, 256), 16, 2, 128, "bf16", 0.3, 4),
+    # The same shapes with a real-time segment (mask rule 2): parity and a bench line of their own.
+    "C2_RT": Config("C2_RT", LAYER_FULL, 64, ("uniform", 128, 512), ("fixed", 32), 8, 2, 64, "bf16", 0.3, 11,
+                    rt=("uniform", 8, 96)),
+    "C3_RT": Config("C3_RT", LAYER_FULL, 256, ("uniform", 512, 1024), ("fixed", 64), 8, 2, 64, "bf16", 0.3, 12,
+                    rt=("uniform", 32, 128)),
+    "C4_RT": Config("C4_RT", LAYER_TARGET, 128, ("fixed", 2048), ("fixed", 128), 16, 4, 64, "bf16", 0.3, 13,
+                    rt=("uniform", 32, 128)),
 }
 
 # stream ids (fixed; part of the recipe)
-_S_HIST, _S_TGT, _S_Q, _S_K, _S_V, _S_DO = 0, 1, 2, 3, 4, 5
+_S_HIST, _S_TGT, _S_Q, _S_K, _S_V, _S_DO, _S_RT, _S_TS = 0, 1, 2, 3, 4, 5, 6, 7
 
 
 def _draw_lengths(spec: tuple, key: np.uint64, batch: int) -> np.ndarray:
@@ -166,6 +183,8 @@ class Case:
     v: np.ndarray              # [total_kv, Hkv, d] float32
     dout: Optional[np.ndarray]  # [total_q, Hq, d] float32 or None
     scale: float
+    rt_len: Optional[np.ndarray] = None      # [B] int32 real-time tokens per user, or None (no such segment)
+    timestamps: Optional[np.ndarray] = None  # [total_kv] int32, one per K/V row, or None
 
     @property
     def total_q(self) -> int:
@@ -195,10 +214,25 @@ def offsets_from_lengths(lengths: np.ndarray) -> np.ndarray:
     return off.astype(np.int32)
 
 
+def _draw_timestamps(key: np.uint64, kv_offsets: np.ndarray, hist_len: np.ndarray, rt_len: np.ndarray) -> np.ndarray:
+    """One integer timestamp per K/V row: uniform in the window of the token's kind, history and real-time
+    segments sorted ascending inside each user."""
+    total = int(kv_offsets[-1])
+    u = uniform01(key, 0, total)
+    ts = np.zeros(total, dtype=np.int32)
+    for b in range(hist_len.shape[0]):
+        s0, L, R, e = int(kv_offsets[b]), int(hist_len[b]), int(rt_len[b]), int(kv_offsets[b + 1])
+        for lo, hi, (w0, w1), sort in ((s0, s0 + L, TS_WINDOW_HIST, True), (s0 + L, s0 + L + R, TS_WINDOW_RT, True),
+                                      (s0 + L + R, e, TS_WINDOW_TGT, False)):
+            seg = (w0 + np.floor(u[lo:hi] * (w1 - w0))).astype(np.int32).clip(w0, w1 - 1)
+            ts[lo:hi] = np.sort(seg) if sort else seg
+    return ts
+
+
 def make_case(cfg: Config, with_dout: bool = True, hist_len: Optional[np.ndarray] = None,
-              n_targets: Optional[np.ndarray] = None) -> Case:
-    """Draw one batch for ``cfg``.  Order of draws: lengths (history, targets), then q, k, v, dout,
-    each tensor from its own stream in memory order.  Explicit ``hist_len`` / ``n_targets``
+              n_targets: Optional[np.ndarray] = None, rt_len: Optional[np.ndarray] = None) -> Case:
+    """Draw one batch for ``cfg``.  Order of draws: lengths (history, targets, real-time), then q, k, v, dout,
+    timestamps, each from its own stream in memory order.  Explicit ``hist_len`` / ``n_targets`` / ``rt_len``
     override the drawn lengths (edge-case tests)."""
     if hist_len is None:
         hist_len = _draw_lengths(cfg.hist, stream_key(cfg.seed, _S_HIST), cfg.batch)
@@ -206,7 +240,11 @@ def make_case(cfg: Config, with_dout: bool = True, hist_len: Optional[np.ndarray
         n_targets = _draw_lengths(cfg.targets, stream_key(cfg.seed, _S_TGT), cfg.batch)
     hist_len = np.asarray(hist_len, dtype=np.int32)
     n_targets = np.asarray(n_targets, dtype=np.int32)
-    kv_offsets = offsets_from_lengths(hist_len + n_targets)
+    has_rt = cfg.rt is not None or rt_len is not None
+    if has_rt and rt_len is None:
+        rt_len = _draw_lengths(cfg.rt, stream_key(cfg.seed, _S_RT), cfg.batch)
+    rt = np.asarray(rt_len, dtype=np.int32) if has_rt else np.zeros_like(hist_len)
+    kv_offsets = offsets_from_lengths(hist_len + rt + n_targets)
     q_offsets = kv_offsets.copy() if cfg.layer == LAYER_FULL else offsets_from_lengths(n_targets)
     tq, tkv = int(q_offsets[-1]), int(kv_offsets[-1])
     q = _values(stream_key(cfg.seed, _S_Q), (tq, cfg.Hq, cfg.head_dim), cfg.std, cfg.dtype)
@@ -215,16 +253,18 @@ def make_case(cfg: Config, with_dout: bool = True, hist_len: Optional[np.ndarray
     dout = None
     if with_dout:
         dout = _values(stream_key(cfg.seed, _S_DO), (tq, cfg.Hq, cfg.head_dim), cfg.dout_std, cfg.dtype)
+    ts = _draw_timestamps(stream_key(cfg.seed, _S_TS), kv_offsets, hist_len, rt) if has_rt else None
     return Case(cfg, hist_len, n_targets, kv_offsets, q_offsets, q, k, v, dout,
-                1.0 / math.sqrt(cfg.head_dim))
+                1.0 / math.sqrt(cfg.head_dim), rt if has_rt else None, ts)
 
 
 def custom_config(name: str, layer: int, hist_len, n_targets, Hq: int, Hkv: int, head_dim: int,
-                  dtype: str = "bf16", std: float = 0.3, seed: int = 1234) -> Config:
+                  dtype: str = "bf16", std: float = 0.3, seed: int = 1234, rt_len=None) -> Config:
     hist_len = list(int(x) for x in hist_len)
     n_targets = list(int(x) for x in n_targets)
+    rt = None if rt_len is None else ("list", list(int(x) for x in rt_len))
     return Config(name, layer, len(hist_len), ("list", hist_len), ("list", n_targets), Hq, Hkv, head_dim,
-                  dtype, std, seed)
+                  dtype, std, seed, rt=rt)
 
 
 def take_users(case: Case, users) -> Case:
@@ -234,10 +274,12 @@ def take_users(case: Case, users) -> Case:
     qrows = np.concatenate([np.arange(case.q_offsets[u], case.q_offsets[u + 1]) for u in users]) if users else np.zeros(0, np.int64)
     kvrows = np.concatenate([np.arange(case.kv_offsets[u], case.kv_offsets[u + 1]) for u in users]) if users else np.zeros(0, np.int64)
     hl, nt = case.hist_len[users], case.n_targets[users]
-    kvo = offsets_from_lengths(hl + nt)
+    rl = None if case.rt_len is None else case.rt_len[users]
+    kvo = offsets_from_lengths(hl + nt + (0 if rl is None else rl))
     qo = kvo.copy() if case.cfg.layer == LAYER_FULL else offsets_from_lengths(nt)
     return Case(case.cfg, hl, nt, kvo, qo, case.q[qrows], case.k[kvrows], case.v[kvrows],
-                None if case.dout is None else case.dout[qrows], case.scale)
+                None if case.dout is None else case.dout[qrows], case.scale, rl,
+                None if case.timestamps is None else case.timestamps[kvrows])
 
 
 def user_rows(offsets: np.ndarray, users) -> np.ndarray:
@@ -270,4 +312,23 @@ def take_kv_group(case: Case, g: int) -> Case:
     return Case(sub, case.hist_len, case.n_targets, case.kv_offsets, case.q_offsets,
                 np.ascontiguousarray(case.q[:, hs]), np.ascontiguousarray(case.k[:, g:g + 1]),
                 np.ascontiguousarray(case.v[:, g:g + 1]),
-                None if case.dout is None else np.ascontiguousarray(case.dout[:, hs]), case.scale)
+                None if case.dout is None else np.ascontiguousarray(case.dout[:, hs]), case.scale, case.rt_len,
+                case.timestamps)
+
+
+def visible_pairs_of(case: Case) -> int:
+    """visible_pairs for a batch that may carry real-time tokens: under rule 2 a real-time key is visible to the
+    queries with a strictly later timestamp and to its own token."""
+    cfg = case.cfg
+    if case.rt_len is None:
+        return visible_pairs(case.hist_len, case.n_targets, cfg.Hq, cfg.layer)
+    total = 0
+    for b in range(case.batch):
+        L, R, T = int(case.hist_len[b]), int(case.rt_len[b]), int(case.n_targets[b])
+        ts = case.timestamps[case.kv_offsets[b]:case.kv_offsets[b + 1]].astype(np.int64)
+        first = 0 if cfg.layer == LAYER_FULL else L + R
+        rows_ts = ts[first:]
+        total += rows_ts.shape[0] * L                                               # rule 1
+        total += int(np.searchsorted(ts[L:L + R], rows_ts, side="left").sum())       # rule 2: strictly earlier keys
+        total += (R if cfg.layer == LAYER_FULL else 0) + T                           # own keys
+    return int(cfg.Hq * total)

@@ -1,0 +1,249 @@
+"""Pins for the oracle's mask rule 2 (real-time tokens, Section 3.2.2): a dense brute force built from token
+kinds and timestamps, hand-worked numbers, reductions to the case without real-time tokens, autograd and
+finite differences, and what the rule implies for who can influence whom.  CPU only."""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import hta_oracle as O
+from paper_2602_11235_amd import inputs
+
+FULL, TARGET = inputs.LAYER_FULL, inputs.LAYER_TARGET
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def dense_mask(L, R, T, ts):
+    """N x N 0/1 matrix built from token kinds: an 'H' column is visible to every row, an 'R' column to the rows
+    whose own timestamp is later and to its own row, a 'T' column only on the diagonal."""
+    kinds = ["H"] * L + ["R"] * R + ["T"] * T
+    N = L + R + T
+    M = np.zeros((N, N), dtype=bool)
+    for j, kind in enumerate(kinds):
+        for i in range(N):
+            if kind == "H":
+                M[i, j] = True
+            elif kind == "R":
+                M[i, j] = (ts[i] > ts[j]) or (i == j)
+            else:
+                M[i, j] = i == j
+    return M
+
+
+def torch_dense(case, layer, need_grads):
+    """out, lse (and gradients by autograd) of an independently written dense masked attention in float64."""
+    cfg = case.cfg
+    r = cfg.Hq // cfg.Hkv
+    q = torch.tensor(case.q, dtype=torch.float64, requires_grad=need_grads)
+    k = torch.tensor(case.k, dtype=torch.float64, requires_grad=need_grads)
+    v = torch.tensor(case.v, dtype=torch.float64, requires_grad=need_grads)
+    out = torch.zeros(case.q.shape, dtype=torch.float64)
+    lse = torch.zeros((cfg.Hq, case.total_q), dtype=torch.float64)
+    loss = 0.0
+    for b in range(case.batch):
+        L, R, T = int(case.hist_len[b]), int(case.rt_len[b]), int(case.n_targets[b])
+        ks, ke = int(case.kv_offsets[b]), int(case.kv_offsets[b + 1])
+        qs, qe = int(case.q_offsets[b]), int(case.q_offsets[b + 1])
+        M = torch.tensor(dense_mask(L, R, T, case.timestamps[ks:ke]))
+        if layer == TARGET:
+            M = M[L + R:]
+        if qe == qs:
+            continue
+        kb = k[ks:ke].repeat_interleave(r, dim=1)
+        vb = v[ks:ke].repeat_interleave(r, dim=1)
+        S = case.scale * torch.einsum("ihd,jhd->hij", q[qs:qe], kb)
+        S = S.masked_fill(~M[None], float("-inf"))
+        P = torch.softmax(S, dim=-1)
+        o = torch.einsum("hij,jhd->ihd", P, vb)
+        out[qs:qe] = o.detach()
+        lse[:, qs:qe] = torch.logsumexp(S, dim=-1).detach()
+        if need_grads:
+            loss = loss + (o * torch.tensor(case.dout[qs:qe], dtype=torch.float64)).sum()
+    if not need_grads:
+        return out.numpy(), lse.numpy()
+    loss.backward()
+    return out.numpy(), lse.numpy(), q.grad.numpy(), k.grad.numpy(), v.grad.numpy()
+
+
+def run_oracle(case, layer=None, with_bwd=False):
+    layer = case.cfg.layer if layer is None else layer
+    out, lse = O.forward(case.q, case.k, case.v, case.q_offsets, case.kv_offsets, case.hist_len, case.n_targets,
+                         case.scale, layer, rt_len=case.rt_len, timestamps=case.timestamps)
+    if not with_bwd:
+        return out, lse
+    dq, dk, dv = O.backward(case.dout, case.q, case.k, case.v, out, lse, case.q_offsets, case.kv_offsets,
+                            case.hist_len, case.n_targets, case.scale, layer, rt_len=case.rt_len,
+                            timestamps=case.timestamps)
+    return out, lse, dq, dk, dv
+
+
+def small_case(layer, hist, rt, tgts, Hq=4, Hkv=2, d=8, seed=21, std=0.7):
+    cfg = inputs.custom_config("small_rt", layer, hist, tgts, Hq, Hkv, d, dtype="fp32", std=std, seed=seed, rt_len=rt)
+    return inputs.make_case(cfg)
+
+
+SHAPES = [([5, 0, 3], [4, 6, 0], [3, 2, 4]), ([9], [7], [5]), ([0, 2], [5, 1], [2, 0])]
+
+
+# ------------------------------------------------------------------ hand-worked numbers
+def test_hand_worked_example_with_realtime_tokens():
+    rows = np.loadtxt(os.path.join(GOLDEN, "hand_worked_hta_realtime.txt"))
+    q = np.ones((5, 1, 1))
+    k = np.log(np.array([1.0, 2.0, 3.0, 5.0, 7.0])).reshape(5, 1, 1)
+    v = np.array([1.0, 2.0, 3.0, 4.0, 5.0]).reshape(5, 1, 1)
+    ts = np.array([0, 5, 7, 6, 8], np.int32)
+    off = np.array([0, 5], np.int32)
+    out, lse = O.forward(q, k, v, off, off, [1], [2], 1.0, FULL, rt_len=[2], timestamps=ts)
+    assert np.allclose(out[:, 0, 0], rows[:, 1], rtol=0, atol=1e-14)
+    assert np.allclose(np.exp(lse[0]), rows[:, 2], rtol=1e-14)
+    out_t, lse_t = O.forward(q[3:], k, v, np.array([0, 2], np.int32), off, [1], [2], 1.0, TARGET, rt_len=[2],
+                             timestamps=ts)
+    assert np.allclose(out_t[:, 0, 0], rows[3:, 1], atol=1e-14) and np.allclose(np.exp(lse_t[0]), rows[3:, 2], rtol=1e-13)
+
+
+# ------------------------------------------------------------------ dense brute force, autograd, differences
+@pytest.mark.parametrize("layer", [FULL, TARGET])
+@pytest.mark.parametrize("hist,rt,tgts", SHAPES)
+def test_forward_and_backward_equal_dense_masked_attention(layer, hist, rt, tgts):
+    case = small_case(layer, hist, rt, tgts)
+    out, lse, dq, dk, dv = run_oracle(case, with_bwd=True)
+    ro, rl, rdq, rdk, rdv = torch_dense(case, layer, True)
+    for got, ref in ((out, ro), (lse, rl), (dq, rdq), (dk, rdk), (dv, rdv)):
+        assert np.allclose(got, ref, rtol=1e-10, atol=1e-12)
+
+
+@pytest.mark.parametrize("layer", [FULL, TARGET])
+def test_backward_equals_central_differences(layer):
+    case = small_case(layer, [3, 1], [3, 2], [2, 2], Hq=2, Hkv=1, d=3)
+
+    def loss(q, k, v):
+        out, _ = O.forward(q, k, v, case.q_offsets, case.kv_offsets, case.hist_len, case.n_targets, case.scale, layer,
+                           rt_len=case.rt_len, timestamps=case.timestamps)
+        return float((out * case.dout).sum())
+
+    _, _, dq, dk, dv = run_oracle(case, with_bwd=True)
+    eps = 1e-6
+    base = [case.q.astype(np.float64), case.k.astype(np.float64), case.v.astype(np.float64)]
+    for which, grad in enumerate((dq, dk, dv)):
+        num = np.zeros_like(grad)
+        for idx in np.ndindex(*grad.shape):
+            hi = [a.copy() for a in base]
+            lo = [a.copy() for a in base]
+            hi[which][idx] += eps
+            lo[which][idx] -= eps
+            num[idx] = (loss(*hi) - loss(*lo)) / (2 * eps)
+        assert np.allclose(grad, num, rtol=2e-6, atol=1e-8)
+
+
+# ------------------------------------------------------------------ reductions to the case without real-time tokens
+def test_no_realtime_tokens_is_the_plain_hybrid_mask():
+    case = small_case(FULL, [4, 0, 6], [0, 0, 0], [3, 2, 0])
+    got = run_oracle(case, with_bwd=True)
+    ref_out, ref_lse = O.forward(case.q, case.k, case.v, case.q_offsets, case.kv_offsets, case.hist_len, case.n_targets,
+                                 case.scale, FULL)
+    ref_g = O.backward(case.dout, case.q, case.k, case.v, ref_out, ref_lse, case.q_offsets, case.kv_offsets,
+                       case.hist_len, case.n_targets, case.scale, FULL)
+    for a, b in zip(got, (ref_out, ref_lse) + tuple(ref_g)):
+        assert np.array_equal(a, b)
+
+
+def test_realtime_tokens_older_than_everything_act_as_history_for_the_targets():
+    """Strictly increasing real-time timestamps below every target timestamp: each target sees all of them, exactly as
+    if they were history tokens."""
+    case = small_case(TARGET, [5], [4], [3])
+    L, R = 5, 4
+    ts = case.timestamps.copy()
+    ts[L:L + R] = np.arange(R) - 100
+    case.timestamps = ts
+    out, lse = run_oracle(case)
+    ref_out, ref_lse = O.forward(case.q, case.k, case.v, case.q_offsets, case.kv_offsets, [L + R], case.n_targets,
+                                 case.scale, TARGET)
+    assert np.allclose(out, ref_out, rtol=1e-13, atol=1e-14) and np.allclose(lse, ref_lse, rtol=1e-13, atol=1e-14)
+
+
+def test_realtime_tokens_newer_than_everything_are_invisible_to_history_and_targets():
+    """Real-time timestamps above every other timestamp: history and target rows come out as if the real-time tokens
+    were not in the sample; the real-time rows see the history, the earlier real-time tokens and themselves."""
+    case = small_case(FULL, [4], [3], [3])
+    L, R, T = 4, 3, 3
+    ts = case.timestamps.copy()
+    ts[L:L + R] = 10_000 + np.arange(R)
+    case.timestamps = ts
+    out, lse = run_oracle(case)
+    keep = np.r_[0:L, L + R:L + R + T]
+    off = np.array([0, L + T], np.int32)
+    ref_out, ref_lse = O.forward(case.q[keep], case.k[keep], case.v[keep], off, off, [L], [T], case.scale, FULL)
+    assert np.allclose(out[keep], ref_out, rtol=1e-13, atol=1e-14) and np.allclose(lse[:, keep], ref_lse, rtol=1e-13)
+    for h in range(case.cfg.Hq):
+        p = O.probs(case.q, case.k, 0, 0, L, T, h, case.scale, FULL, rt_len=R, timestamps=ts)
+        for i in range(R):   # causal inside the real-time segment, own key included
+            assert np.all(p[L + i, :L + i + 1] > 0) and np.all(p[L + i, L + i + 1:] == 0)
+
+
+def test_equal_timestamps_are_not_later():
+    """A real-time token whose timestamp equals the query's is not visible to it (the rule says later)."""
+    case = small_case(FULL, [2], [3], [2])
+    L, R, T = 2, 3, 2
+    ts = np.array([0, 1, 50, 50, 60, 50, 60], np.int32)   # H H | R R R | T T
+    case.timestamps = ts
+    p = O.probs(case.q, case.k, 0, 0, L, T, 0, case.scale, FULL, rt_len=R, timestamps=ts)
+    vis = p > 0
+    # target with time 50 sees no real-time token; the one with time 60 sees the two of time 50, not the one of time 60
+    assert vis[L + R].tolist() == [True, True, False, False, False, True, False]
+    assert vis[L + R + 1].tolist() == [True, True, True, True, False, False, True]
+    # real-time rows: equal times do not see each other, each sees itself; the last one sees both earlier ones
+    assert vis[L].tolist() == [True, True, True, False, False, False, False]
+    assert vis[L + 1].tolist() == [True, True, False, True, False, False, False]
+    assert vis[L + 2].tolist() == [True, True, True, True, True, False, False]
+    # history rows are older than every real-time token here
+    assert vis[0].tolist() == [True, True, False, False, False, False, False]
+    assert np.allclose(p.sum(axis=1), 1.0, atol=1e-14)
+
+
+def test_target_layer_is_row_slice_of_full_layer():
+    full = small_case(FULL, [5, 2], [4, 3], [3, 2])
+    out_f, lse_f = run_oracle(full)
+    cfg_t = inputs.custom_config("small_rt", TARGET, [5, 2], [3, 2], 4, 2, 8, dtype="fp32", std=0.7, seed=21, rt_len=[4, 3])
+    tgt = inputs.make_case(cfg_t)
+    rows = np.concatenate([np.arange(full.kv_offsets[b] + full.hist_len[b] + full.rt_len[b], full.kv_offsets[b + 1])
+                           for b in range(2)])
+    tgt.q = full.q[rows]
+    tgt.k, tgt.v, tgt.timestamps = full.k, full.v, full.timestamps
+    out_t, lse_t = run_oracle(tgt)
+    assert np.allclose(out_t, out_f[rows], rtol=1e-14, atol=1e-15) and np.allclose(lse_t, lse_f[:, rows], rtol=1e-14)
+
+
+# ------------------------------------------------------------------ who can influence whom
+def test_a_realtime_key_gets_gradient_only_from_later_rows_and_its_own():
+    case = small_case(FULL, [3], [4], [3], Hq=2, Hkv=1, d=4)
+    L, R, T = 3, 4, 3
+    ts = case.timestamps
+    _, _, _, dk0, dv0 = run_oracle(case, with_bwd=True)
+    j = L + 1                                   # a real-time key
+    for i in range(L + R + T):
+        changed = case.dout.copy()
+        changed[i] += 1.0
+        case2 = inputs.Case(case.cfg, case.hist_len, case.n_targets, case.kv_offsets, case.q_offsets, case.q, case.k,
+                            case.v, changed, case.scale, case.rt_len, case.timestamps)
+        _, _, _, dk1, dv1 = run_oracle(case2, with_bwd=True)
+        sees = (ts[i] > ts[j]) or (i == j)
+        assert (not np.allclose(dv1[j], dv0[j])) == sees
+        assert (not np.allclose(dk1[j], dk0[j])) == sees
+
+
+def test_visible_pair_count_matches_the_mask():
+    case = small_case(FULL, [6, 0, 3], [5, 4, 0], [3, 2, 4], Hq=2, Hkv=1, d=4)
+    count = 0
+    for b in range(case.batch):
+        ks, ke = int(case.kv_offsets[b]), int(case.kv_offsets[b + 1])
+        count += int(dense_mask(int(case.hist_len[b]), int(case.rt_len[b]), int(case.n_targets[b]),
+                                case.timestamps[ks:ke]).sum())
+    assert inputs.visible_pairs_of(case) == case.cfg.Hq * count
+    for h in range(case.cfg.Hq):
+        p = O.probs(case.q, case.k, 0, 0, int(case.hist_len[0]), int(case.n_targets[0]), h, case.scale, FULL,
+                    rt_len=int(case.rt_len[0]), timestamps=case.timestamps)
+        M = dense_mask(int(case.hist_len[0]), int(case.rt_len[0]), int(case.n_targets[0]),
+                       case.timestamps[:case.kv_offsets[1]])
+        assert np.array_equal(p > 0, M) and np.allclose(p.sum(axis=1), 1.0, atol=1e-14)
