@@ -132,6 +132,42 @@ MTFM_HTA_API int mtfm_hta_validate_host(const int32_t* q_offsets, const int32_t*
                            int32_t max_hist, int32_t max_targets, int layer);
 
 /*
+ * Samples with real-time tokens (mask rule 2 of the dynamic mask, Section 3.2.2: "the R-tokens are visible only to
+ * tokens with later timestamps").  The K/V rows of user b are then hist_len[b] history tokens, rt_len[b] real-time
+ * tokens, n_targets[b] target tokens, in this order (X = (H; R; T), Section 3.2.1); the queries of a full layer are
+ * all of them, those of a target layer the target tokens.  Visibility of key j for query i:
+ *   history key: always (rule 1);   target key: j == i (rule 3);
+ *   real-time key: timestamps[j] < timestamps[i], or j == i (rule 2: later is strict, for every kind of query token;
+ *   a real-time token sees itself, like a target token, so that no row is empty).
+ * Additional arguments, otherwise exactly as the functions without the suffix (which are the case rt_len == 0):
+ *   rt_len      in  [batch] int32 (>= 0)          device pointer
+ *   timestamps  in  [total_kv] int32, one per K/V row; the real-time tokens of a user must be sorted by
+ *               non-decreasing timestamp (history and target tokens in any order)        device pointer
+ *   max_rt      host-known upper bound of rt_len[]
+ *   kv_offsets  prefix sums of hist_len + rt_len + n_targets;  q_offsets == kv_offsets in a full layer
+ * The workspace (mtfm_hta_workspace_bytes_rt) also holds one int32 per query row: the number of leading K/V rows of
+ * its user (history, then the real-time tokens strictly earlier than the row) it attends to; the fp32 path needs
+ * it as well.  mtfm_hta_validate_host_rt additionally checks the order of the real-time timestamps.
+ */
+MTFM_HTA_API size_t mtfm_hta_workspace_bytes_rt(int layer, int dtype, int is_bwd, int32_t batch, int64_t total_q,
+                                int64_t total_kv, int32_t max_hist, int32_t max_rt, int32_t max_targets, int32_t Hq,
+                                int32_t Hkv, int32_t head_dim);
+MTFM_HTA_API int mtfm_hta_fwd_rt(const void* q, const void* k, const void* v, void* out, float* lse,
+                 const int32_t* q_offsets, const int32_t* kv_offsets, const int32_t* hist_len, const int32_t* rt_len,
+                 const int32_t* n_targets, const int32_t* timestamps, int32_t batch, int64_t total_q, int64_t total_kv,
+                 int32_t max_hist, int32_t max_rt, int32_t max_targets, int32_t Hq, int32_t Hkv, int32_t head_dim,
+                 float softmax_scale, int dtype, int layer, void* workspace, size_t workspace_bytes, void* stream);
+MTFM_HTA_API int mtfm_hta_bwd_rt(const void* dout, const void* q, const void* k, const void* v, const void* out,
+                 const float* lse, void* dq, void* dk, void* dv, const int32_t* q_offsets, const int32_t* kv_offsets,
+                 const int32_t* hist_len, const int32_t* rt_len, const int32_t* n_targets, const int32_t* timestamps,
+                 int32_t batch, int64_t total_q, int64_t total_kv, int32_t max_hist, int32_t max_rt,
+                 int32_t max_targets, int32_t Hq, int32_t Hkv, int32_t head_dim, float softmax_scale, int dtype,
+                 int layer, void* workspace, size_t workspace_bytes, void* stream);
+MTFM_HTA_API int mtfm_hta_validate_host_rt(const int32_t* q_offsets, const int32_t* kv_offsets, const int32_t* hist_len,
+                 const int32_t* rt_len, const int32_t* n_targets, const int32_t* timestamps, int32_t batch,
+                 int64_t total_q, int64_t total_kv, int32_t max_hist, int32_t max_rt, int32_t max_targets, int layer);
+
+/*
  * Optional per-kernel timing (benchmarks, profiling).  mtfm_hta_timing_enable(slots) creates `slots`
  * HIP event pairs per kernel kind (slots <= 0: destroy them and switch timing off, the default).  While
  * on, every call records an event pair on its stream around each kernel it enqueues, into a ring of

@@ -22,17 +22,22 @@ int fail(int code, const char* fmt, ...) {
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Workspace {
-    size_t order_off, delta_off, lse_off, total;
+    size_t order_off, delta_off, lse_off, lim_off, total;
 };
 
 // Layout of the caller's workspace (bf16 path; the fp32 debug path needs none):
 //   work counters (256 bytes) and order [batch] int32, users by decreasing tile count; both rebuilt by every call
 //   -delta and -lse/scale, [Hq][total_q] f32 each, the latter followed by one sentinel element   backward only
-Workspace plan_workspace(int dtype, int is_bwd, int32_t batch, int64_t total_q, int32_t Hq) {
-    Workspace w{0, 0, 0, 0};
+//   with real-time tokens (both dtypes): lim [total_q] int32, the per-row limits of mask rule 2, rebuilt by every call
+Workspace plan_workspace(int dtype, int is_bwd, int32_t batch, int64_t total_q, int32_t Hq, bool has_rt) {
+    Workspace w{0, 0, 0, 0, 0};
+    if (has_rt) {
+        w.lim_off = 0;
+        w.total = align256((size_t)total_q * sizeof(int32_t));
+    }
     if (dtype == MTFM_HTA_FP32) return w;
-    w.order_off = 0;
-    w.total = hta::schedule_bytes(batch);
+    w.order_off = w.total;
+    w.total += hta::schedule_bytes(batch);
     if (is_bwd) {
         w.delta_off = w.total;
         w.total += align256((size_t)total_q * Hq * sizeof(float));
@@ -51,14 +56,15 @@ int check_workspace(const Workspace& w, const void* workspace, size_t workspace_
 }
 
 int check_scalars(int layer, int dtype, int32_t batch, int64_t total_q, int64_t total_kv, int32_t max_hist,
-                  int32_t max_targets, int32_t Hq, int32_t Hkv, int32_t d) {
+                  int32_t max_rt, int32_t max_targets, int32_t Hq, int32_t Hkv, int32_t d) {
     if (layer != MTFM_HTA_LAYER_FULL && layer != MTFM_HTA_LAYER_TARGET)
         return fail(MTFM_HTA_ERR_INVALID_ARG, "layer must be MTFM_HTA_LAYER_FULL or MTFM_HTA_LAYER_TARGET, got %d", layer);
     if (dtype != MTFM_HTA_BF16 && dtype != MTFM_HTA_FP32)
         return fail(MTFM_HTA_ERR_INVALID_ARG, "dtype must be MTFM_HTA_BF16 or MTFM_HTA_FP32, got %d", dtype);
-    if (batch < 0 || total_q < 0 || total_kv < 0 || max_hist < 0 || max_targets < 0)
-        return fail(MTFM_HTA_ERR_INVALID_ARG, "negative size (batch %d total_q %lld total_kv %lld max_hist %d max_targets %d)",
-                    batch, (long long)total_q, (long long)total_kv, max_hist, max_targets);
+    if (batch < 0 || total_q < 0 || total_kv < 0 || max_hist < 0 || max_rt < 0 || max_targets < 0)
+        return fail(MTFM_HTA_ERR_INVALID_ARG,
+                    "negative size (batch %d total_q %lld total_kv %lld max_hist %d max_rt %d max_targets %d)", batch,
+                    (long long)total_q, (long long)total_kv, max_hist, max_rt, max_targets);
     if (total_q >= (1ll << 31) || total_kv >= (1ll << 31))
         return fail(MTFM_HTA_ERR_INVALID_ARG, "total_q / total_kv must be below 2^31 (int32 offsets)");
     if (batch > 65535) return fail(MTFM_HTA_ERR_UNSUPPORTED, "batch %d exceeds 65535 users per call", batch);
@@ -71,8 +77,8 @@ int check_scalars(int layer, int dtype, int32_t batch, int64_t total_q, int64_t 
     } else if (!hta::bf16_supported(d, Hq, Hkv)) {
         return fail(MTFM_HTA_ERR_UNSUPPORTED, "bf16 path supports head_dim in {32, 64, 128}, got %d", d);
     }
-    if ((int64_t)max_hist + max_targets >= (1ll << 31))
-        return fail(MTFM_HTA_ERR_INVALID_ARG, "max_hist + max_targets overflows int32");
+    if ((int64_t)max_hist + max_rt + max_targets >= (1ll << 31))
+        return fail(MTFM_HTA_ERR_INVALID_ARG, "max_hist + max_rt + max_targets overflows int32");
     return MTFM_HTA_OK;
 }
 
@@ -88,44 +94,75 @@ const char* mtfm_hta_version(void) { return "0.1.0"; }
 
 size_t mtfm_hta_workspace_bytes(int layer, int dtype, int is_bwd, int32_t batch, int64_t total_q, int64_t total_kv,
                                 int32_t max_hist, int32_t max_targets, int32_t Hq, int32_t Hkv, int32_t head_dim) {
-    if (check_scalars(layer, dtype, batch, total_q, total_kv, max_hist, max_targets, Hq, Hkv, head_dim) != MTFM_HTA_OK)
+    if (check_scalars(layer, dtype, batch, total_q, total_kv, max_hist, 0, max_targets, Hq, Hkv, head_dim) != MTFM_HTA_OK)
         return (size_t)-1;
-    return plan_workspace(dtype, is_bwd, batch, total_q, Hq).total;
+    return plan_workspace(dtype, is_bwd, batch, total_q, Hq, false).total;
 }
 
-int mtfm_hta_validate_host(const int32_t* q_offsets, const int32_t* kv_offsets, const int32_t* hist_len,
-                           const int32_t* n_targets, int32_t batch, int64_t total_q, int64_t total_kv,
-                           int32_t max_hist, int32_t max_targets, int layer) {
+size_t mtfm_hta_workspace_bytes_rt(int layer, int dtype, int is_bwd, int32_t batch, int64_t total_q, int64_t total_kv,
+                                   int32_t max_hist, int32_t max_rt, int32_t max_targets, int32_t Hq, int32_t Hkv,
+                                   int32_t head_dim) {
+    if (check_scalars(layer, dtype, batch, total_q, total_kv, max_hist, max_rt, max_targets, Hq, Hkv, head_dim) != MTFM_HTA_OK)
+        return (size_t)-1;
+    return plan_workspace(dtype, is_bwd, batch, total_q, Hq, true).total;
+}
+
+static int validate_host_impl(const int32_t* q_offsets, const int32_t* kv_offsets, const int32_t* hist_len,
+                              const int32_t* rt_len, const int32_t* n_targets, const int32_t* timestamps, int32_t batch,
+                              int64_t total_q, int64_t total_kv, int32_t max_hist, int32_t max_rt, int32_t max_targets,
+                              int layer) {
     if (batch < 0) return fail(MTFM_HTA_ERR_INVALID_ARG, "negative batch");
     if (layer != MTFM_HTA_LAYER_FULL && layer != MTFM_HTA_LAYER_TARGET)
         return fail(MTFM_HTA_ERR_INVALID_ARG, "bad layer %d", layer);
     if (!q_offsets || !kv_offsets || (batch > 0 && (!hist_len || !n_targets)))
         return fail(MTFM_HTA_ERR_INVALID_ARG, "null array");
+    if (rt_len && !timestamps) return fail(MTFM_HTA_ERR_INVALID_ARG, "rt_len without timestamps");
     if (q_offsets[0] != 0 || kv_offsets[0] != 0) return fail(MTFM_HTA_ERR_INVALID_ARG, "offsets must start at 0");
     for (int32_t b = 0; b < batch; b++) {
-        const int64_t L = hist_len[b], T = n_targets[b];
-        if (L < 0 || T < 0) return fail(MTFM_HTA_ERR_INVALID_ARG, "user %d: negative length", b);
+        const int64_t L = hist_len[b], T = n_targets[b], R = rt_len ? rt_len[b] : 0;
+        if (L < 0 || T < 0 || R < 0) return fail(MTFM_HTA_ERR_INVALID_ARG, "user %d: negative length", b);
         if (L > max_hist) return fail(MTFM_HTA_ERR_INVALID_ARG, "user %d: hist_len %lld > max_hist %d", b, (long long)L, max_hist);
+        if (R > max_rt) return fail(MTFM_HTA_ERR_INVALID_ARG, "user %d: rt_len %lld > max_rt %d", b, (long long)R, max_rt);
         if (T > max_targets)
             return fail(MTFM_HTA_ERR_INVALID_ARG, "user %d: n_targets %lld > max_targets %d", b, (long long)T, max_targets);
-        if ((int64_t)kv_offsets[b + 1] - kv_offsets[b] != L + T)
-            return fail(MTFM_HTA_ERR_INVALID_ARG, "user %d: kv_offsets span != hist_len + n_targets", b);
-        const int64_t rows = layer == MTFM_HTA_LAYER_FULL ? L + T : T;
+        if ((int64_t)kv_offsets[b + 1] - kv_offsets[b] != L + R + T)
+            return fail(MTFM_HTA_ERR_INVALID_ARG, "user %d: kv_offsets span != hist_len + rt_len + n_targets", b);
+        const int64_t rows = layer == MTFM_HTA_LAYER_FULL ? L + R + T : T;
         if ((int64_t)q_offsets[b + 1] - q_offsets[b] != rows)
             return fail(MTFM_HTA_ERR_INVALID_ARG, "user %d: q_offsets span %d != %lld query rows", b,
                         q_offsets[b + 1] - q_offsets[b], (long long)rows);
+        for (int64_t i = 1; i < R; i++)
+            if (timestamps[kv_offsets[b] + L + i] < timestamps[kv_offsets[b] + L + i - 1])
+                return fail(MTFM_HTA_ERR_INVALID_ARG, "user %d: real-time tokens are not sorted by timestamp", b);
     }
     if (q_offsets[batch] != total_q) return fail(MTFM_HTA_ERR_INVALID_ARG, "q_offsets[batch] != total_q");
     if (kv_offsets[batch] != total_kv) return fail(MTFM_HTA_ERR_INVALID_ARG, "kv_offsets[batch] != total_kv");
     return MTFM_HTA_OK;
 }
 
-int mtfm_hta_fwd(const void* q, const void* k, const void* v, void* out, float* lse, const int32_t* q_offsets,
-                 const int32_t* kv_offsets, const int32_t* hist_len, const int32_t* n_targets, int32_t batch,
-                 int64_t total_q, int64_t total_kv, int32_t max_hist, int32_t max_targets, int32_t Hq, int32_t Hkv,
-                 int32_t head_dim, float softmax_scale, int dtype, int layer, void* workspace, size_t workspace_bytes,
-                 void* stream) {
-    int rc = check_scalars(layer, dtype, batch, total_q, total_kv, max_hist, max_targets, Hq, Hkv, head_dim);
+int mtfm_hta_validate_host(const int32_t* q_offsets, const int32_t* kv_offsets, const int32_t* hist_len,
+                           const int32_t* n_targets, int32_t batch, int64_t total_q, int64_t total_kv,
+                           int32_t max_hist, int32_t max_targets, int layer) {
+    return validate_host_impl(q_offsets, kv_offsets, hist_len, nullptr, n_targets, nullptr, batch, total_q, total_kv,
+                              max_hist, 0, max_targets, layer);
+}
+
+int mtfm_hta_validate_host_rt(const int32_t* q_offsets, const int32_t* kv_offsets, const int32_t* hist_len,
+                              const int32_t* rt_len, const int32_t* n_targets, const int32_t* timestamps, int32_t batch,
+                              int64_t total_q, int64_t total_kv, int32_t max_hist, int32_t max_rt, int32_t max_targets,
+                              int layer) {
+    if (!rt_len || !timestamps) return fail(MTFM_HTA_ERR_INVALID_ARG, "null array");
+    return validate_host_impl(q_offsets, kv_offsets, hist_len, rt_len, n_targets, timestamps, batch, total_q, total_kv,
+                              max_hist, max_rt, max_targets, layer);
+}
+
+static int fwd_impl(const void* q, const void* k, const void* v, void* out, float* lse, const int32_t* q_offsets,
+                    const int32_t* kv_offsets, const int32_t* hist_len, const int32_t* rt_len, const int32_t* n_targets,
+                    const int32_t* timestamps, int32_t batch, int64_t total_q, int64_t total_kv, int32_t max_hist,
+                    int32_t max_rt, int32_t max_targets, int32_t Hq, int32_t Hkv, int32_t head_dim, float softmax_scale,
+                    int dtype, int layer, void* workspace, size_t workspace_bytes, void* stream) {
+    const bool has_rt = rt_len != nullptr;
+    int rc = check_scalars(layer, dtype, batch, total_q, total_kv, max_hist, max_rt, max_targets, Hq, Hkv, head_dim);
     if (rc != MTFM_HTA_OK) return rc;
     if (!(softmax_scale > 0.f) || !std::isfinite(softmax_scale))
         return fail(MTFM_HTA_ERR_INVALID_ARG, "softmax_scale must be positive and finite");
@@ -134,7 +171,8 @@ int mtfm_hta_fwd(const void* q, const void* k, const void* v, void* out, float* 
         return fail(MTFM_HTA_ERR_INVALID_ARG, "null pointer argument");
     if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out))
         return fail(MTFM_HTA_ERR_INVALID_ARG, "q, k, v, out must be 16-byte aligned");
-    const Workspace w = plan_workspace(dtype, 0, batch, total_q, Hq);
+    if (has_rt && !timestamps) return fail(MTFM_HTA_ERR_INVALID_ARG, "null pointer argument");
+    const Workspace w = plan_workspace(dtype, 0, batch, total_q, Hq, has_rt);
     rc = check_workspace(w, workspace, workspace_bytes);
     if (rc != MTFM_HTA_OK) return rc;
     hta::Params p{};
@@ -142,9 +180,14 @@ int mtfm_hta_fwd(const void* q, const void* k, const void* v, void* out, float* 
     p.q_off = q_offsets; p.kv_off = kv_offsets; p.hist_len = hist_len; p.n_targets = n_targets;
     p.batch = batch; p.total_q = total_q; p.total_kv = total_kv; p.max_hist = max_hist; p.max_targets = max_targets;
     p.Hq = Hq; p.Hkv = Hkv; p.d = head_dim; p.scale = softmax_scale; p.layer = layer;
+    p.rt_len = rt_len; p.ts = timestamps; p.max_rt = max_rt;
     hipStream_t s = (hipStream_t)stream;
     hipError_t e = hipSuccess;
-    if (dtype == MTFM_HTA_BF16) {
+    if (has_rt) {
+        p.lim = (int32_t*)((char*)workspace + w.lim_off);
+        e = hta::launch_rt_limits(p, s);
+    }
+    if (e == hipSuccess && dtype == MTFM_HTA_BF16) {
         void* region = (char*)workspace + w.order_off;
         e = hta::launch_schedule(p, region, s);
         p.order = hta::schedule_order(region);
@@ -155,12 +198,35 @@ int mtfm_hta_fwd(const void* q, const void* k, const void* v, void* out, float* 
     return MTFM_HTA_OK;
 }
 
-int mtfm_hta_bwd(const void* dout, const void* q, const void* k, const void* v, const void* out, const float* lse,
-                 void* dq, void* dk, void* dv, const int32_t* q_offsets, const int32_t* kv_offsets,
-                 const int32_t* hist_len, const int32_t* n_targets, int32_t batch, int64_t total_q, int64_t total_kv,
-                 int32_t max_hist, int32_t max_targets, int32_t Hq, int32_t Hkv, int32_t head_dim, float softmax_scale,
-                 int dtype, int layer, void* workspace, size_t workspace_bytes, void* stream) {
-    int rc = check_scalars(layer, dtype, batch, total_q, total_kv, max_hist, max_targets, Hq, Hkv, head_dim);
+int mtfm_hta_fwd(const void* q, const void* k, const void* v, void* out, float* lse, const int32_t* q_offsets,
+                 const int32_t* kv_offsets, const int32_t* hist_len, const int32_t* n_targets, int32_t batch,
+                 int64_t total_q, int64_t total_kv, int32_t max_hist, int32_t max_targets, int32_t Hq, int32_t Hkv,
+                 int32_t head_dim, float softmax_scale, int dtype, int layer, void* workspace, size_t workspace_bytes,
+                 void* stream) {
+    return fwd_impl(q, k, v, out, lse, q_offsets, kv_offsets, hist_len, nullptr, n_targets, nullptr, batch, total_q,
+                    total_kv, max_hist, 0, max_targets, Hq, Hkv, head_dim, softmax_scale, dtype, layer, workspace,
+                    workspace_bytes, stream);
+}
+
+int mtfm_hta_fwd_rt(const void* q, const void* k, const void* v, void* out, float* lse, const int32_t* q_offsets,
+                    const int32_t* kv_offsets, const int32_t* hist_len, const int32_t* rt_len, const int32_t* n_targets,
+                    const int32_t* timestamps, int32_t batch, int64_t total_q, int64_t total_kv, int32_t max_hist,
+                    int32_t max_rt, int32_t max_targets, int32_t Hq, int32_t Hkv, int32_t head_dim, float softmax_scale,
+                    int dtype, int layer, void* workspace, size_t workspace_bytes, void* stream) {
+    if (batch > 0 && total_q > 0 && (!rt_len || !timestamps)) return fail(MTFM_HTA_ERR_INVALID_ARG, "null pointer argument");
+    return fwd_impl(q, k, v, out, lse, q_offsets, kv_offsets, hist_len, rt_len, n_targets, timestamps, batch, total_q,
+                    total_kv, max_hist, max_rt, max_targets, Hq, Hkv, head_dim, softmax_scale, dtype, layer, workspace,
+                    workspace_bytes, stream);
+}
+
+static int bwd_impl(const void* dout, const void* q, const void* k, const void* v, const void* out, const float* lse,
+                    void* dq, void* dk, void* dv, const int32_t* q_offsets, const int32_t* kv_offsets,
+                    const int32_t* hist_len, const int32_t* rt_len, const int32_t* n_targets, const int32_t* timestamps,
+                    int32_t batch, int64_t total_q, int64_t total_kv, int32_t max_hist, int32_t max_rt,
+                    int32_t max_targets, int32_t Hq, int32_t Hkv, int32_t head_dim, float softmax_scale, int dtype,
+                    int layer, void* workspace, size_t workspace_bytes, void* stream) {
+    const bool has_rt = rt_len != nullptr;
+    int rc = check_scalars(layer, dtype, batch, total_q, total_kv, max_hist, max_rt, max_targets, Hq, Hkv, head_dim);
     if (rc != MTFM_HTA_OK) return rc;
     if (!(softmax_scale > 0.f) || !std::isfinite(softmax_scale))
         return fail(MTFM_HTA_ERR_INVALID_ARG, "softmax_scale must be positive and finite");
@@ -170,7 +236,8 @@ int mtfm_hta_bwd(const void* dout, const void* q, const void* k, const void* v, 
     if (misaligned(dout) || misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out) || misaligned(dq) ||
         misaligned(dk) || misaligned(dv))
         return fail(MTFM_HTA_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
-    const Workspace w = plan_workspace(dtype, 1, batch, total_q, Hq);
+    if (has_rt && !timestamps) return fail(MTFM_HTA_ERR_INVALID_ARG, "null pointer argument");
+    const Workspace w = plan_workspace(dtype, 1, batch, total_q, Hq, has_rt);
     rc = check_workspace(w, workspace, workspace_bytes);
     if (rc != MTFM_HTA_OK) return rc;
     hta::Params p{};
@@ -179,14 +246,19 @@ int mtfm_hta_bwd(const void* dout, const void* q, const void* k, const void* v, 
     p.q_off = q_offsets; p.kv_off = kv_offsets; p.hist_len = hist_len; p.n_targets = n_targets;
     p.batch = batch; p.total_q = total_q; p.total_kv = total_kv; p.max_hist = max_hist; p.max_targets = max_targets;
     p.Hq = Hq; p.Hkv = Hkv; p.d = head_dim; p.scale = softmax_scale; p.layer = layer;
-    if (w.total > 0) {
+    p.rt_len = rt_len; p.ts = timestamps; p.max_rt = max_rt;
+    if (dtype == MTFM_HTA_BF16) {
         char* base = (char*)workspace;
         p.neg_delta = (float*)(base + w.delta_off);
         p.neg_lse_s = (float*)(base + w.lse_off);
     }
     hipStream_t s = (hipStream_t)stream;
     hipError_t e = hipSuccess;
-    if (dtype == MTFM_HTA_BF16) {
+    if (has_rt) {
+        p.lim = (int32_t*)((char*)workspace + w.lim_off);
+        e = hta::launch_rt_limits(p, s);
+    }
+    if (e == hipSuccess && dtype == MTFM_HTA_BF16) {
         void* region = (char*)workspace + w.order_off;
         e = hta::launch_schedule(p, region, s);
         p.order = hta::schedule_order(region);
@@ -195,6 +267,28 @@ int mtfm_hta_bwd(const void* dout, const void* q, const void* k, const void* v, 
     if (e == hipSuccess) e = dtype == MTFM_HTA_FP32 ? hta::launch_bwd_fp32(p, s) : hta::launch_bwd_bf16(p, s);
     if (e != hipSuccess) return fail(MTFM_HTA_ERR_LAUNCH, "backward launch failed: %s", hipGetErrorString(e));
     return MTFM_HTA_OK;
+}
+
+int mtfm_hta_bwd(const void* dout, const void* q, const void* k, const void* v, const void* out, const float* lse,
+                 void* dq, void* dk, void* dv, const int32_t* q_offsets, const int32_t* kv_offsets,
+                 const int32_t* hist_len, const int32_t* n_targets, int32_t batch, int64_t total_q, int64_t total_kv,
+                 int32_t max_hist, int32_t max_targets, int32_t Hq, int32_t Hkv, int32_t head_dim, float softmax_scale,
+                 int dtype, int layer, void* workspace, size_t workspace_bytes, void* stream) {
+    return bwd_impl(dout, q, k, v, out, lse, dq, dk, dv, q_offsets, kv_offsets, hist_len, nullptr, n_targets, nullptr,
+                    batch, total_q, total_kv, max_hist, 0, max_targets, Hq, Hkv, head_dim, softmax_scale, dtype, layer,
+                    workspace, workspace_bytes, stream);
+}
+
+int mtfm_hta_bwd_rt(const void* dout, const void* q, const void* k, const void* v, const void* out, const float* lse,
+                    void* dq, void* dk, void* dv, const int32_t* q_offsets, const int32_t* kv_offsets,
+                    const int32_t* hist_len, const int32_t* rt_len, const int32_t* n_targets, const int32_t* timestamps,
+                    int32_t batch, int64_t total_q, int64_t total_kv, int32_t max_hist, int32_t max_rt,
+                    int32_t max_targets, int32_t Hq, int32_t Hkv, int32_t head_dim, float softmax_scale, int dtype,
+                    int layer, void* workspace, size_t workspace_bytes, void* stream) {
+    if (batch > 0 && total_kv > 0 && (!rt_len || !timestamps)) return fail(MTFM_HTA_ERR_INVALID_ARG, "null pointer argument");
+    return bwd_impl(dout, q, k, v, out, lse, dq, dk, dv, q_offsets, kv_offsets, hist_len, rt_len, n_targets, timestamps,
+                    batch, total_q, total_kv, max_hist, max_rt, max_targets, Hq, Hkv, head_dim, softmax_scale, dtype, layer,
+                    workspace, workspace_bytes, stream);
 }
 
 }  // extern "C"

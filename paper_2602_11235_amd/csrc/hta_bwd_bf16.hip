@@ -45,7 +45,7 @@ __global__ __launch_bounds__(256) void bwd_self_kernel(Params p) {
     constexpr int LPR = D / 8;           // lanes per item, 8 elements (16 bytes) each
     constexpr int IPB = 256 / LPR;       // items per block
     const int b = blockIdx.z;  // bandwidth-bound pass: user order does not matter
-    const int L = p.hist_len[b], T = p.n_targets[b];
+    const int L = p.hist_len[b] + (p.rt_len ? p.rt_len[b] : 0), T = p.n_targets[b];  // L: tokens before the targets
     const int r = p.Hq / p.Hkv;
     const int item = blockIdx.x * IPB + threadIdx.x / LPR;  // (target, g) flattened, g fastest
     const int sub = threadIdx.x % LPR;
@@ -106,7 +106,9 @@ __global__ __launch_bounds__(256) void bwd_self_kernel(Params p) {
 // ---------------------------------------------------------------------------------------- dQ
 constexpr int BN = 64;  // keys per LDS tile of the dQ kernel
 
-template <int D, int RB, int NW>
+// RT: users with real-time tokens (mask rule 2), handled as in the forward kernel: their keys run through the same
+// tile loop, masked per query row with the row's limit; a real-time row gets its own key in the epilogue.
+template <int D, int RB, int NW, bool RT>
 __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(Params p, int hpb, int n_hc, int tpg) {
     using ST = KvStage<D, NW>;
     constexpr int NKS = D / 16, NDB = D / 32, NKB = BN / 32;
@@ -126,14 +128,15 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(Params p, int hpb, i
     const int b = scheduled_user(p, w.user_slot);
     const int g = w.y / n_hc, hc = w.y % n_hc;
     const int L = p.hist_len[b], T = p.n_targets[b];
-    const int n_rows = p.layer == 0 ? L + T : T;
+    const int LK = L + (RT ? p.rt_len[b] : 0);  // keys that run through the tile loop: history, then real-time
+    const int n_rows = p.layer == 0 ? LK + T : T;
     const int BM = (NW / hpb) * RB * 32;
     const int tile_row0 = w.tile * BM;
     if (tile_row0 >= n_rows) return;  // uniform for the whole workgroup
     const int r = p.Hq / p.Hkv;
     const int h = g * r + hc * hpb + wave % hpb;
     const int wrow0 = tile_row0 + (wave / hpb) * (RB * 32);
-    const int tok_shift = p.layer == 0 ? 0 : L;
+    const int tok_shift = p.layer == 0 ? 0 : LK;
     const int64_t q_base = p.q_off[b], kv_base = p.kv_off[b];
     const __bf16* kg = (const __bf16*)p.k;
     const __bf16* vg = (const __bf16*)p.v;
@@ -142,6 +145,7 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(Params p, int hpb, i
     // per lane: one query row per row block (clamped past the end; never stored then)
     bf16x8 qf[RB][NKS], dof[RB][NKS];
     float lse2[RB], dl[RB];
+    int lim[RB];  // RT: leading keys the lane's row sees
 #pragma unroll
     for (int rb = 0; rb < RB; rb++) {
         int row = wrow0 + rb * 32 + l32;
@@ -160,6 +164,7 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(Params p, int hpb, i
         const float delta = part + other_half(part);
         lse2[rb] = lse * LOG2E;
         dl[rb] = -delta;
+        lim[rb] = RT ? p.lim[q_base + row] : L;
         // every (row, head) belongs to exactly one wave of this kernel: it leaves the row statistics for the dK/dV pass
         if (row_live && hf == 0) {
             p.neg_delta[stat] = -delta;
@@ -174,7 +179,7 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(Params p, int hpb, i
 #pragma unroll
             for (int v = 0; v < 16; v++) dQ[rb][db][v] = 0.f;
 
-    const int n_kt = (L + BN - 1) / BN;
+    const int n_kt = (LK + BN - 1) / BN;
     int nat[NKS], tlo[NDB], thi[NDB];  // per-lane element offsets of the operand fragments inside a swizzled tile
     natural_offsets<D>(nat, lane);
     transposed_offsets<D>(tlo, thi, lane);
@@ -183,7 +188,14 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(Params p, int hpb, i
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     const uint32_t smem_addr = lds_address(smem);
 
-    auto subtile = [&](const __bf16* Ks, const __bf16* Vs, int n_live) {  // Ks, Vs: first row of the sub-tile
+    auto subtile = [&](const __bf16* Ks, const __bf16* Vs, int n_live, int k0) __attribute__((always_inline)) {  // Ks, Vs: first row of the sub-tile (key k0)
+        const bool masked = RT && k0 + 32 > L;  // uniform: the sub-tile holds real-time keys (or runs past the end)
+        if (masked) {
+            bool any = false;
+#pragma unroll
+            for (int rb = 0; rb < RB; rb++) any = any || lim[rb] > k0;
+            if (__builtin_amdgcn_ballot_w64(any) == 0) return;  // no row of this wave sees any key of the sub-tile
+        }
         floatx16 S[RB], dP[RB];  // S^T, dP^T: [key (registers)][row (lanes)]
 #pragma unroll
         for (int ks = 0; ks < NKS; ks++) {
@@ -201,7 +213,16 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(Params p, int hpb, i
                 }
             }
         }
-        if (n_live < 32) {  // ragged: keys >= L_b are not visible (P = 0)
+        if (masked) {  // per row: keys at or past the row's limit are not visible (P = 0)
+            static_for<0, RB>([&](auto Rb) {
+                constexpr int rb = decltype(Rb)::value;
+                const int rel = lim[rb] - k0;
+                static_for<0, 16>([&](auto V) {
+                    constexpr int v = decltype(V)::value;
+                    S[rb][v] = (8 * (v / 4) + 4 * hf + (v % 4) >= rel) ? -INFINITY : S[rb][v];
+                });
+            });
+        } else if (n_live < 32) {  // ragged: keys >= L_b are not visible (P = 0)
 #pragma unroll
             for (int v = 0; v < 16; v++) {
                 if (8 * (v / 4) + 4 * hf + (v % 4) >= n_live) {
@@ -233,9 +254,9 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(Params p, int hpb, i
     // itself; the compiler must not be left with pending loads of its own (Q, dO, lse, delta) that it would wait for
     // inside the loop.
     wait_vmem_loads();
-    if (n_kt > 0) ST::issue(kg, vg, kv_base, p.Hkv, g, L, 0, smem_addr, voff, wave_u, lane);
+    if (n_kt > 0) ST::issue(kg, vg, kv_base, p.Hkv, g, LK, 0, smem_addr, voff, wave_u, lane);
     if (AHEAD > 1 && n_kt > 1) {
-        ST::issue(kg, vg, kv_base, p.Hkv, g, L, 1, smem_addr + ST::BYTES, voff, wave_u, lane);
+        ST::issue(kg, vg, kv_base, p.Hkv, g, LK, 1, smem_addr + ST::BYTES, voff, wave_u, lane);
         wait_vmem_outstanding<ST::COPIES>();
     } else {
         wait_vmem_outstanding<0>();
@@ -243,17 +264,17 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(Params p, int hpb, i
     lds_barrier();
     // Tile t is consumed from stage t % NSTAGE while tile t+AHEAD is fetched into stage (t+AHEAD) % NSTAGE, which was
     // last read for tile t-1, i.e. before the barrier that every wave has passed.
-    auto tile = [&](int t, auto St) {
+    auto tile = [&](int t, auto St) __attribute__((always_inline)) {
         constexpr int st = decltype(St)::value;
         if (t + AHEAD < n_kt)
-            ST::issue(kg, vg, kv_base, p.Hkv, g, L, t + AHEAD, smem_addr + ((st + AHEAD) % NSTAGE) * ST::BYTES, voff, wave_u, lane);
+            ST::issue(kg, vg, kv_base, p.Hkv, g, LK, t + AHEAD, smem_addr + ((st + AHEAD) % NSTAGE) * ST::BYTES, voff, wave_u, lane);
         const __bf16* Ks = (const __bf16*)(smem + st * ST::BYTES);
         const __bf16* Vs = Ks + ST::TILE;
-        const int live = L - t * BN;  // keys of this tile inside the history (>= 1)
+        const int live = LK - t * BN;  // keys of this tile that exist (>= 1)
 #pragma unroll
         for (int kb = 0; kb < NKB; kb++) {
             const int n_live = live - kb * 32;
-            if (n_live > 0) subtile(Ks + kb * 32 * D, Vs + kb * 32 * D, n_live);
+            if (n_live > 0) subtile(Ks + kb * 32 * D, Vs + kb * 32 * D, n_live, t * BN + kb * 32);
         }
         // tile t+1 must have landed; a tile requested after it may stay in flight
         if (AHEAD > 1 && t + 2 < n_kt) wait_vmem_outstanding<ST::COPIES>(); else wait_vmem_outstanding<0>();
@@ -316,21 +337,27 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(Params p, int hpb, i
 }
 
 // ---------------------------------------------------------------------------------------- dK, dV
-template <int D, int NW>
+template <int D, int NW, bool RT>
 struct DkdvSmem {
     static constexpr int UPI = 2;      // (head, 32-row block) units per loop iteration, i.e. per workgroup barrier
     static constexpr int NSTAGE = 3;   // iterations resident in LDS: one being consumed, two in flight
     static constexpr int TILE = 32 * D;                 // one unpadded, swizzled 32-row tile (elements)
-    static constexpr size_t UNIT_BYTES = (size_t)2 * TILE * 2 + 2 * 32 * sizeof(float);  // Q, dO, -lse/scale[32], -delta[32]
+    // Q, dO, -lse/scale[32], -delta[32]; with real-time tokens also the rows' limits, int[32] (written twice)
+    static constexpr size_t UNIT_BYTES = (size_t)2 * TILE * 2 + 2 * 32 * sizeof(float) + (RT ? 256 : 0);
     static constexpr size_t STAGE_BYTES = UPI * UNIT_BYTES;
     static constexpr size_t BYTES = NSTAGE * STAGE_BYTES;
 };
 
 // One workgroup per (user, kv head, tile of NW*32 history keys).  Q and dO tiles travel global -> LDS directly
 // (no register stop-over), two iterations ahead of their use.
-template <int D, int NW>
+// RT: users with real-time tokens (mask rule 2).  Their keys follow the history keys and are owned by waves like any
+// other key; a wave whose 32 keys reach past the history takes the masked instruction stream, where a weight
+// survives only if the key lies below the row's limit (p.lim, staged with the row statistics) or is the row's own
+// token (the own key of a real-time row; target rows' own keys are the business of bwd_self_kernel).
+template <int D, int NW, bool RT>
 __global__ __launch_bounds__(NW * 64, D > 64 ? 1 : 2) void bwd_dkdv_kernel(Params p, int tpg, unsigned per_xcd) {
-    using SM = DkdvSmem<D, NW>;
+    using SM = DkdvSmem<D, NW, RT>;
+    static_assert(!RT || NW >= 2 * SM::UPI, "waves UPI .. 2 UPI - 1 copy the rows' limits");
     constexpr int UPI = SM::UPI, NSTAGE = SM::NSTAGE;
     constexpr int NKS = D / 16, NDB = D / 32;
     constexpr int CPR = D / 8;                  // 16-byte chunks per row
@@ -362,16 +389,18 @@ __global__ __launch_bounds__(NW * 64, D > 64 ? 1 : 2) void bwd_dkdv_kernel(Param
     if (!w.valid) return;
     const int b = scheduled_user(p, w.user_slot), g = w.y;
     const int L = p.hist_len[b], T = p.n_targets[b];
+    const int LK = L + (RT ? p.rt_len[b] : 0);  // keys that receive gradient here: history, then real-time
     const int key0 = w.tile * (NW * 32);
-    if (key0 >= L) return;  // uniform: this key tile does not exist for the user
-    const int n_rows = p.layer == 0 ? L + T : T;
+    if (key0 >= LK) return;  // uniform: this key tile does not exist for the user
+    const int n_rows = p.layer == 0 ? LK + T : T;
+    const int tok_shift = p.layer == 0 ? 0 : LK;  // token index of query row 0
     const int r = p.Hq / p.Hkv;
     const int64_t q_base = p.q_off[b], kv_base = p.kv_off[b];
     const float c2 = p.scale * LOG2E;
     const int kw = key0 + wave * 32;        // first key of this wave
-    const bool wave_live = kw < L;          // a wave past the history only helps staging
-    const bool key_live = kw + l32 < L;
-    const bool wave_ragged = kw + 32 > L;
+    const bool wave_live = kw < LK;         // a wave past the last key only helps staging
+    const bool key_live = kw + l32 < LK;
+    const bool wave_ragged = kw + 32 > L;   // past the end, or (RT) into the real-time keys: masked instruction stream
     const bool copies = IPT >= NW || wave < IPT;   // does this wave issue tile copies?
 
     // per-lane element offsets into a swizzled tile
@@ -394,7 +423,7 @@ __global__ __launch_bounds__(NW * 64, D > 64 ? 1 : 2) void bwd_dkdv_kernel(Param
     // stationary operands: K and V rows of the wave's keys (B operand of S = Q K^T and dP = dO V^T)
     bf16x8 kf[NKS], vf[NKS];
     {
-        const int key = key_live ? kw + l32 : L - 1;
+        const int key = key_live ? kw + l32 : LK - 1;
         const int64_t off = ((kv_base + key) * p.Hkv + g) * D + 8 * hf;
 #pragma unroll
         for (int ks = 0; ks < NKS; ks++) {
@@ -429,6 +458,7 @@ __global__ __launch_bounds__(NW * 64, D > 64 ? 1 : 2) void bwd_dkdv_kernel(Param
         tile_voff[jj] = (uint32_t)((trow * p.Hq * D + (((lane % CPR) ^ swizzle<D>(trow)) << 3)) * 2);
     }
     const float* stat_lane = (hf == 0 ? p.neg_lse_s : p.neg_delta) + q_base + l32;
+    const int32_t* lim_lane = RT ? p.lim + q_base + l32 : nullptr;  // both halves of the wave fetch the same 32 limits
     int iss_rb = 0, iss_hh = 0;
     auto issue_tiles = [&](auto St) {
         const uint32_t stage = lds_address(stage_ptr(St));
@@ -449,6 +479,7 @@ __global__ __launch_bounds__(NW * 64, D > 64 ? 1 : 2) void bwd_dkdv_kernel(Param
                     copy16_global_to_lds_at((const __bf16*)p.dout + ubase, tile_voff[jj], dst + (uint32_t)SM::TILE * 2u);
                 }
                 if (wave_u == uu) copy4_global_to_lds_at(stat_lane + ((int64_t)h * p.total_q + row0), unit + 4u * (uint32_t)SM::TILE);
+                if (RT && wave_u == uu + UPI) copy4_global_to_lds_at(lim_lane + row0, unit + 4u * (uint32_t)SM::TILE + 256u);
             } else {
 #pragma unroll
                 for (int jj = 0; jj < (copies ? IPW : 0); jj++) {
@@ -471,6 +502,11 @@ __global__ __launch_bounds__(NW * 64, D > 64 ? 1 : 2) void bwd_dkdv_kernel(Param
                     const float* src = hf == 0 ? p.neg_lse_s + (dead ? (int64_t)p.Hq * p.total_q : idx) : p.neg_delta + idx;
                     copy4_global_to_lds_at(src, unit + 4u * (uint32_t)SM::TILE);
                 }
+                if (RT && wave_u == uu + UPI) {
+                    int row = row0 + l32;
+                    row = row < n_rows ? row : n_rows - 1;
+                    copy4_global_to_lds_at(p.lim + q_base + row, unit + 4u * (uint32_t)SM::TILE + 256u);
+                }
             }
             if (!past && ++iss_hh == r) {
                 iss_hh = 0;
@@ -481,10 +517,11 @@ __global__ __launch_bounds__(NW * 64, D > 64 ? 1 : 2) void bwd_dkdv_kernel(Param
     // wait until at most the copies this wave has issued for its K most recent iterations are outstanding
     auto wait_all_but_iterations = [&](auto Kc) {
         constexpr int K = decltype(Kc)::value;
+        const bool extra = wave < UPI || (RT && wave < 2 * UPI);  // one more copy per iteration: statistics, or limits
         if (copies) {
-            if (wave < UPI) wait_vmem_outstanding<K * (COPIES + 1)>(); else wait_vmem_outstanding<K * COPIES>();
+            if (extra) wait_vmem_outstanding<K * (COPIES + 1)>(); else wait_vmem_outstanding<K * COPIES>();
         } else {
-            if (wave < UPI) wait_vmem_outstanding<K>(); else wait_vmem_outstanding<0>();
+            if (extra) wait_vmem_outstanding<K>(); else wait_vmem_outstanding<0>();
         }
     };
     const std::integral_constant<int, 0> c0{};
@@ -544,11 +581,32 @@ __global__ __launch_bounds__(NW * 64, D > 64 ? 1 : 2) void bwd_dkdv_kernel(Param
     struct Weights {
         bf16x8 pb[2], dsb[2];
     };
-    auto weights = [&](const Operands& o, Weights& wt, auto ragged) {
+    // `ubase`, `u`: the unit's place in LDS and its number (used by the masked stream only)
+    auto weights = [&](const Operands& o, Weights& wt, auto ragged, const unsigned char* ubase, int u) {
+        constexpr bool MASKED = decltype(ragged)::value;
+        int limv[16];     // RT: limits of the unit's rows, register v <-> row 8(v/4) + 4 hf + v%4
+        int self_row = 0; // RT: the row of the unit whose own token is this lane's key (if it is one of its 32 rows)
+        if constexpr (MASKED && RT) {
+            typedef int int4v __attribute__((ext_vector_type(4)));
+            const int* ls = (const int*)(ubase + (size_t)4 * SM::TILE + 256);
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                const int4v l4 = *(const int4v*)(ls + 8 * j + 4 * hf);
+#pragma unroll
+                for (int i = 0; i < 4; i++) limv[4 * j + i] = l4[i];
+            }
+            self_row = kw + l32 - tok_shift - (u / r) * 32;
+        }
 #pragma unroll
         for (int v = 0; v < 16; v++) {
             float pw = fast_exp2(o.S[v] * c2);
-            if (decltype(ragged)::value) pw = key_live ? pw : 0.f;  // keys past the history carry no weight
+            if constexpr (MASKED && RT) {
+                const int key = kw + l32;
+                const bool vis = key < limv[v] || (key_live && self_row == 8 * (v / 4) + 4 * hf + (v % 4));
+                pw = vis ? pw : 0.f;
+            } else if constexpr (MASKED) {
+                pw = key_live ? pw : 0.f;  // keys past the history carry no weight
+            }
             wt.pb[v / 8][v % 8] = (__bf16)pw;
             wt.dsb[v / 8][v % 8] = (__bf16)(pw * o.dP[v]);
         }
@@ -591,12 +649,12 @@ __global__ __launch_bounds__(NW * 64, D > 64 ? 1 : 2) void bwd_dkdv_kernel(Param
             Weights wt;
             scores(cur);
             load_transposed(base, f);
-            weights(cur, wt, ragged);
+            weights(cur, wt, ragged, base, it * UPI);
             load_operands(base + SM::UNIT_BYTES, nxt);
             accumulate(wt, f);
             scores(nxt);
             load_transposed(base + SM::UNIT_BYTES, f);
-            weights(nxt, wt, ragged);
+            weights(nxt, wt, ragged, base + SM::UNIT_BYTES, it * UPI + 1);
             // copies of iteration it+1 must have landed; those of it+2 may stay in flight
             if (it + 2 < n_iter) wait_all_but_iterations(c1); else wait_all_but_iterations(c0);
             lds_barrier();
@@ -637,7 +695,7 @@ __global__ __launch_bounds__(NW * 64, D > 64 ? 1 : 2) void bwd_dkdv_kernel(Param
 #pragma unroll
         for (int v = 0; v < 16; v++) {
             const int key = kw + 8 * (v / 4) + 4 * hf + (v % 4);
-            if (key < L) {
+            if (key < LK) {
                 const int64_t off = ((kv_base + key) * p.Hkv + g) * D + l32;
 #pragma unroll
                 for (int db = 0; db < NDB; db++) {
@@ -677,22 +735,29 @@ hipError_t launch_dq(const Params& p, hipStream_t s) {
     const int64_t n_rt = (rows + BM - 1) / BM;
     const int64_t n_blocks = work_grid((int64_t)p.batch * p.Hkv * n_hc, n_rt);
     if (n_blocks >= (1ll << 31)) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((bwd_dq_kernel<D, RB, NW>), dim3((unsigned)n_blocks), dim3(NW * 64), 0, s, p, hpb, n_hc, (int)n_rt);
+    auto kernel = p.rt_len ? bwd_dq_kernel<D, RB, NW, true> : bwd_dq_kernel<D, RB, NW, false>;
+    hipLaunchKernelGGL(kernel, dim3((unsigned)n_blocks), dim3(NW * 64), 0, s, p, hpb, n_hc, (int)n_rt);
+    return hipGetLastError();
+}
+
+template <int D, int NW, bool RT>
+hipError_t launch_dkdv_as(const Params& p, hipStream_t s) {
+    const int64_t keys = max_lead_keys(p);
+    if (keys <= 0) return hipSuccess;
+    const int64_t n_kt = (keys + NW * 32 - 1) / (NW * 32);
+    const int64_t n_items = work_grid((int64_t)p.batch * p.Hkv, n_kt);
+    if (n_items >= (1ll << 31)) return hipErrorInvalidValue;
+    const int64_t resident = resident_workgroups<bwd_dkdv_kernel<D, NW, RT>>(NW * 64);
+    Params pk = p;
+    pk.queue = p.queue + QUEUE_DKDV * N_XCD;
+    hipLaunchKernelGGL((bwd_dkdv_kernel<D, NW, RT>), dim3((unsigned)(n_items < resident ? n_items : resident)), dim3(NW * 64),
+                       0, s, pk, (int)n_kt, (unsigned)(n_items / N_XCD));
     return hipGetLastError();
 }
 
 template <int D, int NW>
 hipError_t launch_dkdv(const Params& p, hipStream_t s) {
-    if (p.max_hist <= 0) return hipSuccess;
-    const int64_t n_kt = (p.max_hist + NW * 32 - 1) / (NW * 32);
-    const int64_t n_items = work_grid((int64_t)p.batch * p.Hkv, n_kt);
-    if (n_items >= (1ll << 31)) return hipErrorInvalidValue;
-    const int64_t resident = resident_workgroups<bwd_dkdv_kernel<D, NW>>(NW * 64);
-    Params pk = p;
-    pk.queue = p.queue + QUEUE_DKDV * N_XCD;
-    hipLaunchKernelGGL((bwd_dkdv_kernel<D, NW>), dim3((unsigned)(n_items < resident ? n_items : resident)), dim3(NW * 64), 0, s,
-                       pk, (int)n_kt, (unsigned)(n_items / N_XCD));
-    return hipGetLastError();
+    return p.rt_len ? launch_dkdv_as<D, NW, true>(p, s) : launch_dkdv_as<D, NW, false>(p, s);
 }
 
 template <int D>
@@ -718,7 +783,10 @@ hipError_t launch_bwd_bf16(const Params& p, hipStream_t s) {
     }
     timing_end(MTFM_HTA_KERNEL_BWD_SELF, s);
     if (e != hipSuccess) return e;
-    const bool wide = ((p.Hq / p.Hkv) % 8) == 0;
+    // eight waves of one row block when the head group fills them; with real-time tokens already for groups of four
+    // heads (the masked instruction stream does not fit the register file with two row blocks per wave at d = 64)
+    const int r = p.Hq / p.Hkv;
+    const bool wide = (r % 8) == 0 || (p.rt_len && p.d == 64 && (r % 4) == 0);
     timing_begin(MTFM_HTA_KERNEL_BWD_DQ, s);
     switch (p.d) {
         case 32: e = wide ? launch_dq<32, 2, 8>(p, s) : launch_dq<32, 2, 4>(p, s); break;

@@ -35,12 +35,22 @@ struct Params {
     float* neg_lse_s;     // [Hq][total_q]   -lse_i / scale: what the S accumulators of the dK/dV pass start from
     const int32_t* order; // [batch] users by decreasing tile count (bf16 path), or null = identity
     int32_t* queue;       // [N_XCD] work counters of the kernel being launched (bf16 path), zero when it starts
+    // real-time tokens (mask rule 2); all null / 0 for samples of history + target tokens only
+    const int32_t* rt_len;  // [B] real-time tokens of each user, between its history and its target tokens
+    const int32_t* ts;      // [total_kv] one timestamp per K/V row
+    int32_t max_rt;
+    int32_t* lim;           // [total_q] carved out of the workspace: number of leading K/V rows of the user (history, then
+                            // the real-time tokens strictly earlier than the query) that the query row sees
 };
 
 // number of query rows a user can have at most, from the host-known bounds
 inline int64_t max_query_rows(const Params& p) {
-    return p.layer == 0 ? (int64_t)p.max_hist + p.max_targets : (int64_t)p.max_targets;
+    return p.layer == 0 ? (int64_t)p.max_hist + p.max_rt + p.max_targets : (int64_t)p.max_targets;
 }
+// number of keys a user's tile loops can reach at most: history, then real-time tokens
+inline int64_t max_lead_keys(const Params& p) { return (int64_t)p.max_hist + p.max_rt; }
+// per-row limits of mask rule 2 (a launch of its own at the start of a call with real-time tokens)
+hipError_t launch_rt_limits(const Params& p, hipStream_t s);
 
 hipError_t launch_fwd_fp32(const Params& p, hipStream_t s);
 hipError_t launch_bwd_fp32(const Params& p, hipStream_t s);

@@ -2,9 +2,11 @@
 // (query row, query head).  It exists to check the jagged indexing, the hybrid mask and the
 // C ABI independently of the MFMA kernels; it is not tuned.
 //
-// Mask rules 1 and 3 (Section 3.2.2): the keys a query token `tok` may attend to are the L_b history
-// tokens, plus itself when it is a target token (tok >= L_b).  So the visible keys of a row are the
-// list [0, L_b) followed by at most one more entry, `tok` itself.
+// Mask rules (Section 3.2.2): the keys a query token `tok` may attend to are the L_b history tokens
+// (rule 1), the real-time tokens strictly earlier than it (rule 2; a prefix of the time-sorted real-time
+// segment that follows the history), plus itself when it is a real-time or target token (tok >= L_b).  So
+// the visible keys of a row are the list [0, lead) followed by at most one more entry, `tok` itself, with
+// lead = L_b without real-time tokens and the precomputed per-row limit otherwise.
 #include "../../include/mtfm_hta.h"
 #include "hta_common.h"
 
@@ -26,21 +28,21 @@ struct RowInfo {
     bool valid;
     int64_t q_row;     // row in the packed q/out tensors
     int64_t kv_base;   // first K/V row of the user
-    int32_t L;         // history length
+    int32_t L;         // leading K/V rows of the user that the row sees
     int32_t tok;       // token index of the query inside the user's sample
     int32_t n_vis;     // number of visible keys
 };
 
 __device__ inline RowInfo locate_row(const Params& p, int b, int64_t row) {
     RowInfo r;
-    const int32_t L = p.hist_len[b], T = p.n_targets[b];
-    const int64_t n_rows = p.layer == 0 ? (int64_t)L + T : T;
+    const int32_t L = p.hist_len[b], T = p.n_targets[b], R = p.rt_len ? p.rt_len[b] : 0;
+    const int64_t n_rows = p.layer == 0 ? (int64_t)L + R + T : T;
     r.valid = row < n_rows;
-    r.L = L;
-    r.tok = p.layer == 0 ? (int32_t)row : L + (int32_t)row;
+    r.tok = p.layer == 0 ? (int32_t)row : L + R + (int32_t)row;
     r.q_row = (int64_t)p.q_off[b] + row;
     r.kv_base = p.kv_off[b];
-    r.n_vis = L + (r.tok >= L ? 1 : 0);
+    r.L = (p.lim && r.valid) ? p.lim[r.q_row] : L;
+    r.n_vis = r.L + (r.tok >= L ? 1 : 0);
     return r;
 }
 

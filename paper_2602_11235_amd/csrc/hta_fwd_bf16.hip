@@ -26,7 +26,11 @@ namespace {
 constexpr int BN = 64;  // keys per LDS tile
 constexpr float RESCALE_SLACK = 8.f;  // log2 units a row's logits may exceed its softmax reference before a rescale
 
-template <int D, int RB, int NW>
+// RT: the users carry real-time tokens (mask rule 2).  Their keys follow the history keys in the K/V rows and run through
+// the same tile loop; a sub-tile that reaches past the history is masked per query row with the row's limit
+// (p.lim: history + the real-time tokens strictly earlier than the row), and a real-time row gets its own key in the
+// epilogue exactly like a target row.
+template <int D, int RB, int NW, bool RT>
 __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb, int n_hc, int tpg) {
     using ST = KvStage<D, NW>;
     constexpr int NKS = D / 16, NDB = D / 32, NKB = BN / 32;
@@ -44,14 +48,15 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb,
     const int b = scheduled_user(p, w.user_slot);
     const int g = w.y / n_hc, hc = w.y % n_hc;
     const int L = p.hist_len[b], T = p.n_targets[b];
-    const int n_rows = p.layer == 0 ? L + T : T;
+    const int LK = L + (RT ? p.rt_len[b] : 0);  // keys that run through the tile loop: history, then real-time
+    const int n_rows = p.layer == 0 ? LK + T : T;
     const int BM = (NW / hpb) * RB * 32;
     const int tile_row0 = w.tile * BM;
     if (tile_row0 >= n_rows) return;  // uniform for the whole workgroup
     const int r = p.Hq / p.Hkv;
     const int h = g * r + hc * hpb + wave % hpb;
     const int wrow0 = tile_row0 + (wave / hpb) * (RB * 32);
-    const int tok_shift = p.layer == 0 ? 0 : L;  // token index of query row 0
+    const int tok_shift = p.layer == 0 ? 0 : LK;  // token index of query row 0
     const int64_t q_base = p.q_off[b], kv_base = p.kv_off[b];
     const __bf16* qg = (const __bf16*)p.q;
     const __bf16* kg = (const __bf16*)p.k;
@@ -61,6 +66,7 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb,
     // Q fragments (B operand of S^T = K Q^T): lane = query row, 8 consecutive d values per k-step.
     // Rows past the end of the user are clamped to the last row; their results are never stored.
     bf16x8 qf[RB][NKS];
+    int lim[RB];  // RT: leading keys the lane's row sees
 #pragma unroll
     for (int rb = 0; rb < RB; rb++) {
         int row = wrow0 + rb * 32 + l32;
@@ -68,6 +74,7 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb,
         const __bf16* qp = qg + ((q_base + row) * p.Hq + h) * D + 8 * hf;
 #pragma unroll
         for (int ks = 0; ks < NKS; ks++) qf[rb][ks] = *(const bf16x8*)(qp + ks * 16);
+        lim[rb] = RT ? p.lim[q_base + row] : L;
     }
 
     float m[RB], l[RB];
@@ -82,7 +89,7 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb,
             for (int v = 0; v < 16; v++) O[rb][db][v] = 0.f;
     }
 
-    const int n_kt = (L + BN - 1) / BN;
+    const int n_kt = (LK + BN - 1) / BN;
     int nat[NKS], tlo[NDB], thi[NDB];  // per-lane element offsets of the operand fragments inside a swizzled tile
     natural_offsets<D>(nat, lane);
     transposed_offsets<D>(tlo, thi, lane);
@@ -91,9 +98,16 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb,
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     const uint32_t smem_addr = lds_address(smem);
 
-    // One online-softmax step over a 32-key sub-tile.  `n_live` = number of keys of the sub-tile that are
-    // inside the history (32 except in the ragged last tile).
-    auto subtile = [&](const __bf16* Ks, const __bf16* Vs, int n_live) {  // Ks, Vs: first row of the sub-tile
+    // One online-softmax step over a 32-key sub-tile that starts at key k0.  `n_live` = number of keys of the sub-tile
+    // that exist (32 except in the ragged last tile).
+    auto subtile = [&](const __bf16* Ks, const __bf16* Vs, int n_live, int k0) __attribute__((always_inline)) {  // Ks, Vs: first row of the sub-tile
+        const bool masked = RT && k0 + 32 > L;  // uniform: the sub-tile holds real-time keys (or runs past the end)
+        if (masked) {
+            bool any = false;
+#pragma unroll
+            for (int rb = 0; rb < RB; rb++) any = any || lim[rb] > k0;
+            if (__builtin_amdgcn_ballot_w64(any) == 0) return;  // no row of this wave sees any key of the sub-tile
+        }
         // S^T[key][row] = sum_d K[key][d] Q[row][d]
         floatx16 S[RB];
 #pragma unroll
@@ -106,7 +120,16 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb,
 #pragma unroll
             for (int rb = 0; rb < RB; rb++) S[rb] = mfma32(kf, qf[rb][ks], S[rb]);
         }
-        if (n_live < 32) {  // ragged: keys >= L_b are not visible
+        if (masked) {  // per row: keys at or past the row's limit are not visible
+            static_for<0, RB>([&](auto Rb) {
+                constexpr int rb = decltype(Rb)::value;
+                const int rel = lim[rb] - k0;
+                static_for<0, 16>([&](auto V) {
+                    constexpr int v = decltype(V)::value;
+                    S[rb][v] = (8 * (v / 4) + 4 * hf + (v % 4) >= rel) ? -INFINITY : S[rb][v];
+                });
+            });
+        } else if (n_live < 32) {  // ragged: keys >= L_b are not visible
 #pragma unroll
             for (int v = 0; v < 16; v++) {
                 if (8 * (v / 4) + 4 * hf + (v % 4) >= n_live) {
@@ -130,7 +153,8 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb,
             const bool grow = mx > m[rb] + RESCALE_SLACK;
             if (__builtin_amdgcn_ballot_w64(grow) != 0) {
                 const float m_new = grow ? mx : m[rb];
-                const float alpha = fast_exp2(m[rb] - m_new);  // 1 for the rows that keep their reference
+                // 1 for the rows that keep their reference (which may still be -inf when rows see different keys)
+                const float alpha = grow ? fast_exp2(m[rb] - m_new) : 1.f;
                 m[rb] = m_new;
                 l[rb] *= alpha;
 #pragma unroll
@@ -138,7 +162,8 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb,
 #pragma unroll
                     for (int v = 0; v < 16; v++) O[rb][db][v] *= alpha;
             }
-            const float mref = m[rb];
+            // (a row that has seen no key yet has the reference -inf and only masked logits: keep -inf - -inf out)
+            const float mref = RT ? fmaxf(m[rb], -1e30f) : m[rb];
 #pragma unroll
             for (int v = 0; v < 16; v++) pf[rb][v / 8][v % 8] = (__bf16)fast_exp2(fmaf(S[rb][v], c2, -mref));
             // the row sum uses the same rounded weights as the P V product
@@ -162,9 +187,9 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb,
     // itself; the compiler must not be left with pending loads of its own (the Q fragments) that it would wait for
     // inside the loop.
     wait_vmem_loads();
-    if (n_kt > 0) ST::issue(kg, vg, kv_base, p.Hkv, g, L, 0, smem_addr, voff, wave_u, lane);
+    if (n_kt > 0) ST::issue(kg, vg, kv_base, p.Hkv, g, LK, 0, smem_addr, voff, wave_u, lane);
     if (AHEAD > 1 && n_kt > 1) {
-        ST::issue(kg, vg, kv_base, p.Hkv, g, L, 1, smem_addr + ST::BYTES, voff, wave_u, lane);
+        ST::issue(kg, vg, kv_base, p.Hkv, g, LK, 1, smem_addr + ST::BYTES, voff, wave_u, lane);
         wait_vmem_outstanding<ST::COPIES>();
     } else {
         wait_vmem_outstanding<0>();
@@ -172,17 +197,17 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb,
     lds_barrier();
     // Tile t is consumed from stage t % NSTAGE while tile t+AHEAD is fetched into stage (t+AHEAD) % NSTAGE, which was
     // last read for tile t-1, i.e. before the barrier that every wave has passed.
-    auto tile = [&](int t, auto St) {
+    auto tile = [&](int t, auto St) __attribute__((always_inline)) {
         constexpr int st = decltype(St)::value;
         if (t + AHEAD < n_kt)
-            ST::issue(kg, vg, kv_base, p.Hkv, g, L, t + AHEAD, smem_addr + ((st + AHEAD) % NSTAGE) * ST::BYTES, voff, wave_u, lane);
+            ST::issue(kg, vg, kv_base, p.Hkv, g, LK, t + AHEAD, smem_addr + ((st + AHEAD) % NSTAGE) * ST::BYTES, voff, wave_u, lane);
         const __bf16* Ks = (const __bf16*)(smem + st * ST::BYTES);
         const __bf16* Vs = Ks + ST::TILE;
-        const int live = L - t * BN;  // keys of this tile inside the history (>= 1)
+        const int live = LK - t * BN;  // keys of this tile that exist (>= 1)
 #pragma unroll
         for (int kb = 0; kb < NKB; kb++) {
             const int n_live = live - kb * 32;
-            if (n_live > 0) subtile(Ks + kb * 32 * D, Vs + kb * 32 * D, n_live);
+            if (n_live > 0) subtile(Ks + kb * 32 * D, Vs + kb * 32 * D, n_live, t * BN + kb * 32);
         }
         // tile t+1 must have landed; a tile requested after it may stay in flight
         if (AHEAD > 1 && t + 2 < n_kt) wait_vmem_outstanding<ST::COPIES>(); else wait_vmem_outstanding<0>();
@@ -196,7 +221,7 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb,
         }
     }
 
-    // epilogue: self key of target rows (rule 3), normalisation, stores
+    // epilogue: own key of target rows (rule 3) and of real-time rows, normalisation, stores
     __bf16* og = (__bf16*)p.out;
 #pragma unroll
     for (int rb = 0; rb < RB; rb++) {
@@ -251,6 +276,7 @@ int gcd(int a, int b) { return b == 0 ? a : gcd(b, a % b); }
 
 template <int D, int RB, int NW>
 hipError_t launch(const Params& p, hipStream_t s) {
+    auto kernel = p.rt_len ? fwd_bf16_kernel<D, RB, NW, true> : fwd_bf16_kernel<D, RB, NW, false>;
     const int r = p.Hq / p.Hkv;
     const int hpb = gcd(r, NW);
     const int n_hc = r / hpb;
@@ -260,7 +286,7 @@ hipError_t launch(const Params& p, hipStream_t s) {
     const int64_t n_rt = (rows + BM - 1) / BM;
     const int64_t n_blocks = work_grid((int64_t)p.batch * p.Hkv * n_hc, n_rt);
     if (n_blocks >= (1ll << 31)) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((fwd_bf16_kernel<D, RB, NW>), dim3((unsigned)n_blocks), dim3(NW * 64), 0, s, p, hpb, n_hc, (int)n_rt);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)n_blocks), dim3(NW * 64), 0, s, p, hpb, n_hc, (int)n_rt);
     return hipGetLastError();
 }
 

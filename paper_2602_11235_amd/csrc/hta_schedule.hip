@@ -68,7 +68,34 @@ __global__ __launch_bounds__(SCHED_THREADS) void schedule_bucket_kernel(Params p
     }
 }
 
+// Mask rule 2 (Section 3.2.2): a real-time token is visible only to tokens with later timestamps.  The real-time
+// segment of a user is sorted by time, so the real-time keys a query sees are a prefix of it: those strictly earlier
+// than the query.  lim[row] = hist_len + that prefix length = the number of leading K/V rows of the user the row
+// attends to in the tile loops (its own key, when it is a real-time or target token, is a separate term).
+__global__ __launch_bounds__(256) void rt_limits_kernel(Params p) {
+    const int b = blockIdx.z;
+    const int row = blockIdx.x * 256 + threadIdx.x;
+    const int L = p.hist_len[b], R = p.rt_len[b], T = p.n_targets[b];
+    const int n_rows = p.layer == 0 ? L + R + T : T;
+    if (row >= n_rows) return;
+    const int32_t* ts = p.ts + p.kv_off[b];
+    const int32_t t = ts[p.layer == 0 ? row : L + R + row];
+    int lo = 0, hi = R;  // first real-time token that is not strictly earlier than t
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (ts[L + mid] < t) lo = mid + 1; else hi = mid;
+    }
+    p.lim[(int64_t)p.q_off[b] + row] = L + lo;
+}
+
 }  // namespace
+
+hipError_t launch_rt_limits(const Params& p, hipStream_t s) {
+    const int64_t rows = max_query_rows(p);
+    if (p.batch <= 0 || rows <= 0) return hipSuccess;
+    hipLaunchKernelGGL(rt_limits_kernel, dim3((unsigned)((rows + 255) / 256), 1, (unsigned)p.batch), dim3(256), 0, s, p);
+    return hipGetLastError();
+}
 
 size_t schedule_bytes(int32_t batch) {
     return QUEUE_WORDS * sizeof(int32_t) + ((((size_t)batch * sizeof(int32_t)) + 255) & ~(size_t)255);

@@ -18,6 +18,7 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_LAUNCH = 0, -1, -2, -3,
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmtfm_hta.so")
 EXPORTS = ("mtfm_hta_workspace_bytes", "mtfm_hta_fwd", "mtfm_hta_bwd", "mtfm_hta_validate_host",
+           "mtfm_hta_workspace_bytes_rt", "mtfm_hta_fwd_rt", "mtfm_hta_bwd_rt", "mtfm_hta_validate_host_rt",
            "mtfm_hta_last_error", "mtfm_hta_version", "mtfm_hta_timing_enable", "mtfm_hta_timing_read")
 KERNEL_FWD, KERNEL_BWD_SELF, KERNEL_BWD_DQ, KERNEL_BWD_DKDV = 0, 1, 2, 3
 
@@ -50,6 +51,16 @@ def load_library() -> ctypes.CDLL:
     lib.mtfm_hta_bwd.argtypes = [vp] * 13 + tail
     lib.mtfm_hta_validate_host.restype = ci
     lib.mtfm_hta_validate_host.argtypes = [vp, vp, vp, vp, i32, i64, i64, i32, i32, ci]
+    # samples with real-time tokens: rt_len / timestamps pointers and max_rt are extra
+    lib.mtfm_hta_workspace_bytes_rt.restype = sz
+    lib.mtfm_hta_workspace_bytes_rt.argtypes = [ci, ci, ci, i32, i64, i64, i32, i32, i32, i32, i32, i32]
+    tail_rt = [i32, i64, i64, i32, i32, i32, i32, i32, i32, f32, ci, ci, vp, sz, vp]
+    lib.mtfm_hta_fwd_rt.restype = ci
+    lib.mtfm_hta_fwd_rt.argtypes = [vp] * 11 + tail_rt
+    lib.mtfm_hta_bwd_rt.restype = ci
+    lib.mtfm_hta_bwd_rt.argtypes = [vp] * 15 + tail_rt
+    lib.mtfm_hta_validate_host_rt.restype = ci
+    lib.mtfm_hta_validate_host_rt.argtypes = [vp] * 6 + [i32, i64, i64, i32, i32, i32, ci]
     lib.mtfm_hta_last_error.restype = ctypes.c_char_p
     lib.mtfm_hta_last_error.argtypes = []
     lib.mtfm_hta_version.restype = ctypes.c_char_p
@@ -142,13 +153,52 @@ def mtfm_hta_bwd(dout, q, k, v, out, lse, dq, dk, dv, q_offsets, kv_offsets, his
                                        _stream_handle(stream)))
 
 
+def mtfm_hta_workspace_bytes_rt(layer, dtype, is_bwd, batch, total_q, total_kv, max_hist, max_rt, max_targets, Hq,
+                                Hkv, head_dim) -> int:
+    n = load_library().mtfm_hta_workspace_bytes_rt(layer, dtype, int(is_bwd), batch, total_q, total_kv, max_hist,
+                                                   max_rt, max_targets, Hq, Hkv, head_dim)
+    if n == ctypes.c_size_t(-1).value:
+        raise HtaError(ERR_INVALID_ARG, mtfm_hta_last_error())
+    return int(n)
+
+
+def mtfm_hta_validate_host_rt(q_offsets, kv_offsets, hist_len, rt_len, n_targets, timestamps, batch, total_q,
+                              total_kv, max_hist, max_rt, max_targets, layer) -> None:
+    """Arguments are CPU int32 tensors (or NumPy arrays converted by the caller)."""
+    _check(load_library().mtfm_hta_validate_host_rt(_ptr(q_offsets), _ptr(kv_offsets), _ptr(hist_len), _ptr(rt_len),
+                                                    _ptr(n_targets), _ptr(timestamps), batch, total_q, total_kv,
+                                                    max_hist, max_rt, max_targets, layer))
+
+
+def mtfm_hta_fwd_rt(q, k, v, out, lse, q_offsets, kv_offsets, hist_len, rt_len, n_targets, timestamps, batch,
+                    total_q, total_kv, max_hist, max_rt, max_targets, Hq, Hkv, head_dim, softmax_scale, dtype, layer,
+                    workspace=None, workspace_bytes=0, stream=None) -> None:
+    """Forward pass for samples with real-time tokens (mask rule 2)."""
+    _check(load_library().mtfm_hta_fwd_rt(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), _ptr(q_offsets),
+                                          _ptr(kv_offsets), _ptr(hist_len), _ptr(rt_len), _ptr(n_targets),
+                                          _ptr(timestamps), batch, total_q, total_kv, max_hist, max_rt, max_targets,
+                                          Hq, Hkv, head_dim, softmax_scale, dtype, layer, _ptr(workspace),
+                                          workspace_bytes, _stream_handle(stream)))
+
+
+def mtfm_hta_bwd_rt(dout, q, k, v, out, lse, dq, dk, dv, q_offsets, kv_offsets, hist_len, rt_len, n_targets,
+                    timestamps, batch, total_q, total_kv, max_hist, max_rt, max_targets, Hq, Hkv, head_dim,
+                    softmax_scale, dtype, layer, workspace=None, workspace_bytes=0, stream=None) -> None:
+    """Backward pass for samples with real-time tokens (mask rule 2)."""
+    _check(load_library().mtfm_hta_bwd_rt(_ptr(dout), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), _ptr(dq),
+                                          _ptr(dk), _ptr(dv), _ptr(q_offsets), _ptr(kv_offsets), _ptr(hist_len),
+                                          _ptr(rt_len), _ptr(n_targets), _ptr(timestamps), batch, total_q, total_kv,
+                                          max_hist, max_rt, max_targets, Hq, Hkv, head_dim, softmax_scale, dtype,
+                                          layer, _ptr(workspace), workspace_bytes, _stream_handle(stream)))
+
+
 # --------------------------------------------------------------------------- buffer plumbing
 class Batch:
     """Device buffers of one jagged batch plus the host-known scalars the C ABI wants.  Allocation and
     marshalling only; ``forward`` / ``backward`` call straight into the library."""
 
     def __init__(self, q, k, v, q_offsets, kv_offsets, hist_len, n_targets, max_hist, max_targets, softmax_scale,
-                 layer):
+                 layer, rt_len=None, timestamps=None, max_rt=0):
         assert q.is_cuda and k.is_cuda and v.is_cuda, "HTA runs on the GPU only"
         assert q.dtype in (torch.bfloat16, torch.float32) and k.dtype == q.dtype and v.dtype == q.dtype
         assert q.is_contiguous() and k.is_contiguous() and v.is_contiguous()
@@ -160,12 +210,17 @@ class Batch:
         self.total_q, self.Hq, self.head_dim = int(q.shape[0]), int(q.shape[1]), int(q.shape[2])
         self.total_kv, self.Hkv = int(k.shape[0]), int(k.shape[1])
         self.max_hist, self.max_targets = int(max_hist), int(max_targets)
+        assert (rt_len is None) == (timestamps is None)
+        self.rt_len, self.timestamps, self.max_rt = rt_len, timestamps, int(max_rt)
+        if rt_len is not None:
+            for t in (rt_len, timestamps):
+                assert t.is_cuda and t.dtype == torch.int32 and t.is_contiguous()
         self.softmax_scale, self.layer = float(softmax_scale), int(layer)
         self.dtype = BF16 if q.dtype == torch.bfloat16 else FP32
         self.out = torch.empty_like(q)
         self.lse = torch.empty((self.Hq, self.total_q), dtype=torch.float32, device=q.device)
         self.dq = self.dk = self.dv = None
-        self.fwd_workspace_bytes = mtfm_hta_workspace_bytes(self.layer, self.dtype, False, *self._sizes())
+        self.fwd_workspace_bytes = self._workspace_bytes(False)
         self.fwd_workspace = None
         if self.fwd_workspace_bytes:
             self.fwd_workspace = torch.empty(self.fwd_workspace_bytes, dtype=torch.uint8, device=q.device)
@@ -173,19 +228,31 @@ class Batch:
         self.workspace_bytes = 0
 
     def _sizes(self):
-        return (self.batch, self.total_q, self.total_kv, self.max_hist, self.max_targets, self.Hq, self.Hkv,
-                self.head_dim)
+        if self.rt_len is None:
+            return (self.batch, self.total_q, self.total_kv, self.max_hist, self.max_targets, self.Hq, self.Hkv,
+                    self.head_dim)
+        return (self.batch, self.total_q, self.total_kv, self.max_hist, self.max_rt, self.max_targets, self.Hq,
+                self.Hkv, self.head_dim)
+
+    def _workspace_bytes(self, is_bwd: bool) -> int:
+        fn = mtfm_hta_workspace_bytes if self.rt_len is None else mtfm_hta_workspace_bytes_rt
+        return fn(self.layer, self.dtype, is_bwd, *self._sizes())
 
     def forward(self, stream=None) -> Tuple[torch.Tensor, torch.Tensor]:
-        mtfm_hta_fwd(self.q, self.k, self.v, self.out, self.lse, self.q_offsets, self.kv_offsets, self.hist_len,
-                     self.n_targets, *self._sizes(), self.softmax_scale, self.dtype, self.layer, self.fwd_workspace,
-                     self.fwd_workspace_bytes, stream)
+        if self.rt_len is None:
+            mtfm_hta_fwd(self.q, self.k, self.v, self.out, self.lse, self.q_offsets, self.kv_offsets, self.hist_len,
+                         self.n_targets, *self._sizes(), self.softmax_scale, self.dtype, self.layer,
+                         self.fwd_workspace, self.fwd_workspace_bytes, stream)
+        else:
+            mtfm_hta_fwd_rt(self.q, self.k, self.v, self.out, self.lse, self.q_offsets, self.kv_offsets, self.hist_len,
+                            self.rt_len, self.n_targets, self.timestamps, *self._sizes(), self.softmax_scale,
+                            self.dtype, self.layer, self.fwd_workspace, self.fwd_workspace_bytes, stream)
         return self.out, self.lse
 
     def prepare_backward(self) -> None:
         if self.dq is None:
             self.dq, self.dk, self.dv = torch.empty_like(self.q), torch.empty_like(self.k), torch.empty_like(self.v)
-            self.workspace_bytes = mtfm_hta_workspace_bytes(self.layer, self.dtype, True, *self._sizes())
+            self.workspace_bytes = self._workspace_bytes(True)
             if self.workspace_bytes:
                 self.workspace = torch.empty(self.workspace_bytes, dtype=torch.uint8, device=self.q.device)
                 assert self.workspace.data_ptr() % 256 == 0
@@ -193,7 +260,13 @@ class Batch:
     def backward(self, dout, stream=None):
         assert dout.is_cuda and dout.dtype == self.q.dtype and dout.shape == self.q.shape and dout.is_contiguous()
         self.prepare_backward()
-        mtfm_hta_bwd(dout, self.q, self.k, self.v, self.out, self.lse, self.dq, self.dk, self.dv, self.q_offsets,
-                     self.kv_offsets, self.hist_len, self.n_targets, *self._sizes(), self.softmax_scale, self.dtype,
-                     self.layer, self.workspace, self.workspace_bytes, stream)
+        if self.rt_len is None:
+            mtfm_hta_bwd(dout, self.q, self.k, self.v, self.out, self.lse, self.dq, self.dk, self.dv, self.q_offsets,
+                         self.kv_offsets, self.hist_len, self.n_targets, *self._sizes(), self.softmax_scale,
+                         self.dtype, self.layer, self.workspace, self.workspace_bytes, stream)
+        else:
+            mtfm_hta_bwd_rt(dout, self.q, self.k, self.v, self.out, self.lse, self.dq, self.dk, self.dv,
+                            self.q_offsets, self.kv_offsets, self.hist_len, self.rt_len, self.n_targets,
+                            self.timestamps, *self._sizes(), self.softmax_scale, self.dtype, self.layer,
+                            self.workspace, self.workspace_bytes, stream)
         return self.dq, self.dk, self.dv

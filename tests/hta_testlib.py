@@ -29,9 +29,13 @@ def device_batch(case: inputs.Case) -> hta.Batch:
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to("cuda")
     max_hist = int(case.hist_len.max()) if case.batch else 0
     max_tgt = int(case.n_targets.max()) if case.batch else 0
+    rt = {}
+    if case.rt_len is not None:   # samples with real-time tokens (mask rule 2)
+        rt = dict(rt_len=dev(case.rt_len), timestamps=dev(case.timestamps),
+                  max_rt=int(case.rt_len.max()) if case.batch else 0)
     return hta.Batch(to_torch(case.q, dt), to_torch(case.k, dt), to_torch(case.v, dt), dev(case.q_offsets),
                      dev(case.kv_offsets), dev(case.hist_len), dev(case.n_targets), max_hist, max_tgt, case.scale,
-                     case.cfg.layer)
+                     case.cfg.layer, **rt)
 
 
 def host(t: torch.Tensor) -> np.ndarray:
@@ -40,14 +44,15 @@ def host(t: torch.Tensor) -> np.ndarray:
 
 def oracle_all(case: inputs.Case, with_bwd: bool):
     layer = case.cfg.layer
+    rt = dict(rt_len=case.rt_len, timestamps=case.timestamps)
     out, lse = O.forward(case.q, case.k, case.v, case.q_offsets, case.kv_offsets, case.hist_len, case.n_targets,
-                         case.scale, layer)
+                         case.scale, layer, **rt)
     if not with_bwd:
         return out, lse
     # the backward is fed the *oracle's* forward results: the GPU backward is checked against the exact
     # gradient, not against a gradient contaminated by its own forward rounding
     dq, dk, dv = O.backward(case.dout, case.q, case.k, case.v, out, lse, case.q_offsets, case.kv_offsets,
-                            case.hist_len, case.n_targets, case.scale, layer)
+                            case.hist_len, case.n_targets, case.scale, layer, **rt)
     return out, lse, dq, dk, dv
 
 
