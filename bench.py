@@ -29,7 +29,11 @@ def log(msg: str) -> None:
     print(msg, file=sys.stderr, flush=True)
 
 
-def history_pairs(case) -> int:
+def history_pairs(case, inputs) -> int:
+    """Visible (query, key, head) triples whose key is not the query's own target key: what the dK/dV pass owns."""
+    if case.rt_len is not None:
+        own = case.n_targets.astype(np.int64).sum() * case.cfg.Hq
+        return inputs.visible_pairs_of(case) - int(own)
     L = case.hist_len.astype(np.int64)
     T = case.n_targets.astype(np.int64)
     rows = L + T if case.cfg.layer == 0 else T
@@ -44,20 +48,21 @@ def cpu_baseline(case, inputs, budget_s: float):
     def run(users):
         sub = inputs.take_users(case, users)
         t0 = time.perf_counter()
+        rt = dict(rt_len=sub.rt_len, timestamps=sub.timestamps)
         out, lse = O.forward(sub.q, sub.k, sub.v, sub.q_offsets, sub.kv_offsets, sub.hist_len, sub.n_targets,
-                             sub.scale, sub.cfg.layer)
+                             sub.scale, sub.cfg.layer, **rt)
         O.backward(sub.dout, sub.q, sub.k, sub.v, out, lse, sub.q_offsets, sub.kv_offsets, sub.hist_len,
-                   sub.n_targets, sub.scale, sub.cfg.layer)
+                   sub.n_targets, sub.scale, sub.cfg.layer, **rt)
         dt = time.perf_counter() - t0
-        pairs = inputs.visible_pairs(sub.hist_len, sub.n_targets, sub.cfg.Hq, sub.cfg.layer)
+        pairs = inputs.visible_pairs_of(sub)
         return dt, pairs, sub.batch
 
     O.num_threads()  # loads (and if needed builds) the oracle before timing
     probe_dt, probe_pairs, _ = run(range(min(2, case.batch)))
     per_pair = probe_dt / max(probe_pairs, 1)
-    L = case.hist_len.astype(np.int64)
+    L = case.hist_len.astype(np.int64) + (0 if case.rt_len is None else case.rt_len.astype(np.int64))
     T = case.n_targets.astype(np.int64)
-    per_user = case.cfg.Hq * ((L + T) * L + T if case.cfg.layer == 0 else T * L + T)
+    per_user = case.cfg.Hq * ((L + T) * L + T if case.cfg.layer == 0 else T * L + T)  # upper bound with real-time tokens
     n = int(np.searchsorted(np.cumsum(per_user * per_pair), budget_s)) + 1
     n = max(2, min(n, case.batch))
     dt, pairs, users = run(range(n))
@@ -121,9 +126,12 @@ def main() -> int:
         t = torch.from_numpy(np.ascontiguousarray(x)).to("cuda:0")
         return t.to(torch.bfloat16) if cfg.dtype == "bf16" and t.dtype == torch.float32 else t
 
+    rt = {}
+    if case.rt_len is not None:  # samples with real-time tokens: the *_rt entry points
+        rt = dict(rt_len=dev(case.rt_len), timestamps=dev(case.timestamps), max_rt=int(case.rt_len.max()))
     batch = hta.Batch(dev(case.q), dev(case.k), dev(case.v), dev(case.q_offsets), dev(case.kv_offsets),
                       dev(case.hist_len), dev(case.n_targets), int(case.hist_len.max()), int(case.n_targets.max()),
-                      case.scale, cfg.layer)
+                      case.scale, cfg.layer, **rt)
     dout = dev(case.dout)
     batch.prepare_backward()
     torch.cuda.synchronize()
@@ -155,8 +163,8 @@ def main() -> int:
     hta.mtfm_hta_timing_enable(0)
 
     d = cfg.head_dim
-    pairs = inputs.visible_pairs(case.hist_len, case.n_targets, cfg.Hq, cfg.layer)
-    hist_pairs = history_pairs(case)
+    pairs = inputs.visible_pairs_of(case)
+    hist_pairs = history_pairs(case, inputs)
     ms_per_step = elapsed / args.steps * 1e3
     flops_step = 14.0 * d * pairs
     value = flops_step / (ms_per_step * 1e-3) / 1e12
@@ -194,7 +202,7 @@ def main() -> int:
         "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: B={cfg.batch} hist={cfg.hist} targets={cfg.targets} Hq={cfg.Hq} "
+        "config": {"workload": f"{cfg.name}: B={cfg.batch} hist={cfg.hist}{'' if cfg.rt is None else f' realtime={cfg.rt}'} targets={cfg.targets} Hq={cfg.Hq} "
                                f"Hkv={cfg.Hkv} head_dim={d} layer={'full' if cfg.layer == 0 else 'target'} fwd+bwd",
                    "seed": cfg.seed, "visible_pairs": pairs, "total_tokens": case.total_kv},
         "samples_per_s": case.batch / (ms_per_step * 1e-3),

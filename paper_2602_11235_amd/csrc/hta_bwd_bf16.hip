@@ -783,10 +783,8 @@ hipError_t launch_bwd_bf16(const Params& p, hipStream_t s) {
     }
     timing_end(MTFM_HTA_KERNEL_BWD_SELF, s);
     if (e != hipSuccess) return e;
-    // eight waves of one row block when the head group fills them; with real-time tokens already for groups of four
-    // heads (the masked instruction stream does not fit the register file with two row blocks per wave at d = 64)
-    const int r = p.Hq / p.Hkv;
-    const bool wide = (r % 8) == 0 || (p.rt_len && p.d == 64 && (r % 4) == 0);
+    // eight waves of one row block when the head group fills them, else four waves of two
+    const bool wide = ((p.Hq / p.Hkv) % 8) == 0;
     timing_begin(MTFM_HTA_KERNEL_BWD_DQ, s);
     switch (p.d) {
         case 32: e = wide ? launch_dq<32, 2, 8>(p, s) : launch_dq<32, 2, 4>(p, s); break;
