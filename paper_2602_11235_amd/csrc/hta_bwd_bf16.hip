@@ -142,6 +142,19 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(Params p, int hpb, i
     const __bf16* vg = (const __bf16*)p.v;
     const float c2 = p.scale * LOG2E;
 
+    const int n_kt = (LK + BN - 1) / BN;
+    int nat[NKS], tlo[NDB], thi[NDB];  // per-lane element offsets of the operand fragments inside a swizzled tile
+    natural_offsets<D>(nat, lane);
+    transposed_offsets<D>(tlo, thi, lane);
+    uint32_t voff[ST::COPIES];
+    ST::lane_offsets(voff, p.Hkv, wave, lane);
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const uint32_t smem_addr = lds_address(smem);
+
+    // the first K/V tiles are requested before the row operands are loaded and delta is formed: their latencies overlap
+    if (n_kt > 0) ST::issue(kg, vg, kv_base, p.Hkv, g, LK, 0, smem_addr, voff, wave_u, lane);
+    if (AHEAD > 1 && n_kt > 1) ST::issue(kg, vg, kv_base, p.Hkv, g, LK, 1, smem_addr + ST::BYTES, voff, wave_u, lane);
+
     // per lane: one query row per row block (clamped past the end; never stored then)
     bf16x8 qf[RB][NKS], dof[RB][NKS];
     float lse2[RB], dl[RB];
@@ -178,15 +191,6 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(Params p, int hpb, i
         for (int db = 0; db < NDB; db++)
 #pragma unroll
             for (int v = 0; v < 16; v++) dQ[rb][db][v] = 0.f;
-
-    const int n_kt = (LK + BN - 1) / BN;
-    int nat[NKS], tlo[NDB], thi[NDB];  // per-lane element offsets of the operand fragments inside a swizzled tile
-    natural_offsets<D>(nat, lane);
-    transposed_offsets<D>(tlo, thi, lane);
-    uint32_t voff[ST::COPIES];
-    ST::lane_offsets(voff, p.Hkv, wave, lane);
-    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-    const uint32_t smem_addr = lds_address(smem);
 
     auto subtile = [&](const __bf16* Ks, const __bf16* Vs, int n_live, int k0) __attribute__((always_inline)) {  // Ks, Vs: first row of the sub-tile (key k0)
         const bool masked = RT && k0 + 32 > L;  // uniform: the sub-tile holds real-time keys (or runs past the end)
@@ -251,16 +255,9 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(Params p, int hpb, i
     };
 
     // From here on the only vector-memory traffic of the loop are the asynchronous copies, which this code counts
-    // itself; the compiler must not be left with pending loads of its own (Q, dO, lse, delta) that it would wait for
-    // inside the loop.
+    // itself; the compiler must not be left with pending loads of its own (Q, dO, O, lse) that it would wait for
+    // inside the loop.  (The first tiles were requested before those loads.)
     wait_vmem_loads();
-    if (n_kt > 0) ST::issue(kg, vg, kv_base, p.Hkv, g, LK, 0, smem_addr, voff, wave_u, lane);
-    if (AHEAD > 1 && n_kt > 1) {
-        ST::issue(kg, vg, kv_base, p.Hkv, g, LK, 1, smem_addr + ST::BYTES, voff, wave_u, lane);
-        wait_vmem_outstanding<ST::COPIES>();
-    } else {
-        wait_vmem_outstanding<0>();
-    }
     lds_barrier();
     // Tile t is consumed from stage t % NSTAGE while tile t+AHEAD is fetched into stage (t+AHEAD) % NSTAGE, which was
     // last read for tile t-1, i.e. before the barrier that every wave has passed.
@@ -439,9 +436,6 @@ __global__ __launch_bounds__(NW * 64, D > 64 ? 1 : 2) void bwd_dkdv_kernel(Param
             dK[db][v] = 0.f;
             dV[db][v] = 0.f;
         }
-    // From here on the only vector-memory traffic of the loop are the asynchronous copies, which this code counts
-    // itself; the compiler must not be left with pending loads of its own that it would wait for inside the loop.
-    wait_vmem_loads();
 
     const int n_rb = (n_rows + 31) / 32;
     const int n_units = n_rb * r;  // unit u = (32-row block u / r, head g*r + u % r)
@@ -526,7 +520,6 @@ __global__ __launch_bounds__(NW * 64, D > 64 ? 1 : 2) void bwd_dkdv_kernel(Param
     };
     const std::integral_constant<int, 0> c0{};
     const std::integral_constant<int, 1> c1{};
-    const std::integral_constant<int, 2> c2i{};
 
     // The wave's work on one (head, 32-row block) unit against its 32 keys, in four steps that the loop below
     // interleaves across units: fetch the operands, S and dP, the weights, the two accumulations.
@@ -626,13 +619,14 @@ __global__ __launch_bounds__(NW * 64, D > 64 ? 1 : 2) void bwd_dkdv_kernel(Param
     const std::integral_constant<int, 1> st1{};
     const std::integral_constant<int, 2> st2{};
     static_assert(UPI == 2, "the loop below is written out for two units per iteration");
-    // prologue: all three stages requested, the first one complete
+    // prologue: all three stages requested while the K/V fragments are still on their way (one memory latency instead
+    // of two at the start of every item).  From the wait on, the only vector-memory traffic of the loop are the
+    // asynchronous copies, which this code counts itself; the compiler must not be left with pending loads of its own
+    // that it would wait for inside the loop.
     if (n_iter > 0) issue_tiles(st0);
     if (n_iter > 1) issue_tiles(st1);
     if (n_iter > 2) issue_tiles(st2);
-    if (n_iter > 2) wait_all_but_iterations(c2i);
-    else if (n_iter > 1) wait_all_but_iterations(c1);
-    else wait_all_but_iterations(c0);
+    wait_vmem_loads();
     lds_barrier();
 
     // Iteration `it` consumes stage it % 3.  Its barrier sits in the middle of the second unit, after the last LDS read

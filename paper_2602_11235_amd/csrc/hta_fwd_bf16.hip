@@ -183,17 +183,13 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb,
             }
     };
 
-    // From here on the only vector-memory traffic of the loop are the asynchronous copies, which this code counts
-    // itself; the compiler must not be left with pending loads of its own (the Q fragments) that it would wait for
-    // inside the loop.
-    wait_vmem_loads();
+    // The first tiles are requested while the Q fragments are still on their way: one memory latency instead of two
+    // at the start of every workgroup.  From the wait on, the only vector-memory traffic of the loop are the
+    // asynchronous copies, which this code counts itself; the compiler must not be left with pending loads of its own
+    // (the Q fragments) that it would wait for inside the loop.
     if (n_kt > 0) ST::issue(kg, vg, kv_base, p.Hkv, g, LK, 0, smem_addr, voff, wave_u, lane);
-    if (AHEAD > 1 && n_kt > 1) {
-        ST::issue(kg, vg, kv_base, p.Hkv, g, LK, 1, smem_addr + ST::BYTES, voff, wave_u, lane);
-        wait_vmem_outstanding<ST::COPIES>();
-    } else {
-        wait_vmem_outstanding<0>();
-    }
+    if (AHEAD > 1 && n_kt > 1) ST::issue(kg, vg, kv_base, p.Hkv, g, LK, 1, smem_addr + ST::BYTES, voff, wave_u, lane);
+    wait_vmem_loads();
     lds_barrier();
     // Tile t is consumed from stage t % NSTAGE while tile t+AHEAD is fetched into stage (t+AHEAD) % NSTAGE, which was
     // last read for tile t-1, i.e. before the barrier that every wave has passed.
