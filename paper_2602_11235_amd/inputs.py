@@ -332,3 +332,46 @@ def visible_pairs_of(case: Case) -> int:
         total += int(np.searchsorted(ts[L:L + R], rows_ts, side="left").sum())       # rule 2: strictly earlier keys
         total += (R if cfg.layer == LAYER_FULL else 0) + T                           # own keys
     return int(cfg.Hq * total)
+
+
+# ----------------------------------------------------------------------------- group layer normalization
+@dataclasses.dataclass
+class GlnCase:
+    """Inputs of one group-layer-normalization call: tokens of several groups (history / real-time sequences,
+    scenarios) whose features follow different distributions, which is what the group-wise parameters are for."""
+    name: str
+    dtype: str                 # 'bf16' | 'fp32'
+    x: np.ndarray              # [n_tokens, d_model] float32, exactly representable in dtype
+    gate: Optional[np.ndarray]  # [n_tokens, d_model] or None
+    dy: np.ndarray             # [n_tokens, d_model]
+    group_id: np.ndarray       # [n_tokens] int32
+    gamma: np.ndarray          # [n_groups, d_model] float32
+    beta: np.ndarray           # [n_groups, d_model] float32
+    eps: float
+
+
+_S_GLN_X, _S_GLN_U, _S_GLN_DY, _S_GLN_G, _S_GLN_GAMMA, _S_GLN_BETA, _S_GLN_STATS = 20, 21, 22, 23, 24, 25, 26
+
+
+def make_gln_case(name: str, n_tokens: int, d_model: int, n_groups: int, dtype: str = "bf16", gated: bool = True,
+                  seed: int = 100, eps: float = 1e-5) -> GlnCase:
+    """Group ids are uniform over the groups (tokens of all sequences are interleaved by time, Section 3.2.1); the
+    features of group g are N(mu_g, sigma_g^2) with mu_g ~ U(-1, 1), sigma_g ~ U(0.5, 2); gamma ~ 1 + 0.2 N(0,1),
+    beta ~ 0.2 N(0,1) in float32; gate and upstream gradient ~ N(0, 1)."""
+    gid = np.minimum((uniform01(stream_key(seed, _S_GLN_G), 0, n_tokens) * n_groups).astype(np.int32), n_groups - 1)
+    st = uniform01(stream_key(seed, _S_GLN_STATS), 0, 2 * n_groups)
+    mu, sigma = 2.0 * st[:n_groups] - 1.0, 0.5 + 1.5 * st[n_groups:]
+    z = normal(stream_key(seed, _S_GLN_X), n_tokens * d_model, dtype=np.float32, scale=1.0).reshape(n_tokens, d_model)
+    x = (z.astype(np.float64) * sigma[gid][:, None] + mu[gid][:, None]).astype(np.float32)
+    dy = normal(stream_key(seed, _S_GLN_DY), n_tokens * d_model, dtype=np.float32, scale=1.0).reshape(n_tokens, d_model)
+    gate = None
+    if gated:
+        gate = normal(stream_key(seed, _S_GLN_U), n_tokens * d_model, dtype=np.float32, scale=1.0).reshape(n_tokens, d_model)
+    if dtype == "bf16":
+        x = bf16_bits_to_f32(f32_to_bf16_bits(x)).reshape(n_tokens, d_model)
+        dy = bf16_bits_to_f32(f32_to_bf16_bits(dy)).reshape(n_tokens, d_model)
+        if gate is not None:
+            gate = bf16_bits_to_f32(f32_to_bf16_bits(gate)).reshape(n_tokens, d_model)
+    gamma = (1.0 + normal(stream_key(seed, _S_GLN_GAMMA), n_groups * d_model, dtype=np.float32, scale=0.2)).astype(np.float32)
+    beta = normal(stream_key(seed, _S_GLN_BETA), n_groups * d_model, dtype=np.float32, scale=0.2)
+    return GlnCase(name, dtype, x, gate, dy, gid, gamma.reshape(n_groups, d_model), beta.reshape(n_groups, d_model), eps)
