@@ -10,6 +10,7 @@ float64 CPU oracle timed on a bounded sample of the same workload.
 from __future__ import annotations
 
 import argparse
+import dataclasses
 import json
 import os
 import sys
@@ -75,10 +76,10 @@ def cpu_baseline(case, inputs, budget_s: float):
     }
 
 
-def recorded_traffic(workload: str, kernel: str):
+def recorded_traffic(workload: str, kernel: str, family: str = "hta_fwd_bwd"):
     """HBM bytes per launch of `kernel` on `workload`, as recorded by the committed rocprofv3 counter summary
     (FETCH_SIZE / WRITE_SIZE cannot be read from inside this process); None when there is no record."""
-    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", f"{workload.lower()}_hta_fwd_bwd_kernels.txt")
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", f"{workload.lower()}_{family}_kernels.txt")
     try:
         with open(path) as f:
             for line in f:
@@ -92,8 +93,110 @@ def recorded_traffic(workload: str, kernel: str):
     return None
 
 
+def bench_gln(args) -> int:
+    """--op gln: one step = the gated fused group layer normalization, forward + backward, over all tokens of the
+    headline batch at the model width of its heads (d_model = Hq * head_dim).  HBM-bound: the line reports GB/s of
+    algorithmic bytes (each operand read once, each result written once) against the 8 TB/s peak."""
+    import torch
+    from paper_2602_11235_amd import gln, hta, inputs
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    gln.load_library()
+    cfg = inputs.CONFIGS[args.config]
+    lens = inputs.make_case(dataclasses.replace(cfg, Hq=1, Hkv=1, head_dim=8, dtype="fp32"))  # token count only
+    n, d, groups = int(lens.total_kv), cfg.Hq * cfg.head_dim, args.groups
+    t0 = time.perf_counter()
+    case = inputs.make_gln_case(f"{cfg.name}_gln", n, d, groups, dtype="bf16", gated=True, seed=cfg.seed)
+    log(f"[bench] generated {n} tokens x {d} features, {groups} groups in {time.perf_counter() - t0:.1f} s")
+
+    def dev(a, bf16=False):
+        t = torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+        return t.to(torch.bfloat16) if bf16 else t
+
+    x, u, dy = dev(case.x, True), dev(case.gate, True), dev(case.dy, True)
+    gid, gamma, beta = dev(case.group_id), dev(case.gamma), dev(case.beta)
+    y = torch.empty_like(x)
+    out = (torch.empty_like(x), torch.empty_like(gamma), torch.empty_like(gamma), torch.empty_like(x))
+    ws = torch.empty(gln.mtfm_gln_bwd_workspace_bytes(d, groups), dtype=torch.uint8, device="cuda:0")
+    stats = {}
+
+    def step():
+        _, stats["mean"], stats["rstd"] = gln.mtfm_gln_fwd(x, gid, gamma, beta, case.eps, gate=u, y=y)
+        gln.mtfm_gln_bwd(dy, x, gid, gamma, beta, stats["mean"], stats["rstd"], gate=u, workspace=ws, out=out)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    hta.mtfm_hta_timing_enable(args.steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    kinds = {"gln_fwd": gln.KERNEL_FWD, "gln_bwd": gln.KERNEL_BWD, "gln_bwd_reduce": gln.KERNEL_BWD_REDUCE}
+    kernel_ms = {k: hta.mtfm_hta_timing_read(v) for k, v in kinds.items()}
+    hta.mtfm_hta_timing_enable(0)
+
+    # algorithmic bytes per token: forward reads x, u and writes y (2 bytes each per feature), reads the group id
+    # and writes two statistics; backward reads dy, x, u, writes dx, du, reads the id and the statistics
+    bytes_fwd, bytes_bwd = n * (6 * d + 12), n * (10 * d + 12)
+    alg = {"gln_fwd": bytes_fwd, "gln_bwd": bytes_bwd}
+    ms_per_step = elapsed / args.steps * 1e3
+    kernels = {}
+    for name, ms in kernel_ms.items():
+        if ms:
+            kernels[name] = {"avg_ms": float(np.mean(ms)), "min_ms": float(np.min(ms)), "launches": len(ms)}
+            if name in alg:
+                kernels[name]["gb_per_s"] = alg[name] / (kernels[name]["avg_ms"] * 1e-3) / 1e9
+                kernels[name]["frac_of_hbm_peak"] = kernels[name]["gb_per_s"] / HBM_PEAK_GBS
+    dominant = max(alg, key=lambda k: kernels[k]["avg_ms"])
+    roofline = {"bound": "hbm", "kernel": dominant, "achieved": kernels[dominant]["gb_per_s"], "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": kernels[dominant]["gb_per_s"] / HBM_PEAK_GBS, "traffic": None,
+                "avg_kernel_ms": kernels[dominant]["avg_ms"], "algorithmic_bytes_per_launch": alg[dominant]}
+    measured = recorded_traffic(cfg.name, dominant, "gln")
+    if measured is not None:
+        roofline["traffic"] = measured["read_bytes"] + measured["write_bytes"]
+        roofline["traffic_note"] = (f"HBM bytes per launch (read {measured['read_bytes']}, written "
+                                    f"{measured['write_bytes']}) from the rocprofv3 counter runs recorded in "
+                                    f"{measured['source']}; not measured by this run")
+    value = (bytes_fwd + bytes_bwd) / (ms_per_step * 1e-3) / 1e9
+    result = {
+        "metric": "fused GLN(A)*U fwd+bwd GB/s of algorithmic bytes over the tokens of the headline batch; % of HBM peak",
+        "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name}_gln: {n} tokens (all tokens of {cfg.name}) d_model={d} n_groups={groups} "
+                               "bf16 storage, gated, fwd+bwd", "seed": cfg.seed},
+        "tokens_per_s": n / (ms_per_step * 1e-3), "frac_of_hbm_peak": value / HBM_PEAK_GBS,
+        "kernels": kernels, "roofline": roofline,
+    }
+    if args.cpu_seconds > 0:
+        from oracle import gln_oracle as G
+        log("[bench] timing the float64 oracle on a bounded sample ...")
+        m = min(n, 2000)
+        t0 = time.perf_counter()
+        G.forward(case.x[:m], case.group_id[:m], case.gamma, case.beta, case.eps, case.gate[:m])
+        G.backward(case.dy[:m], case.x[:m], case.group_id[:m], case.gamma, case.beta, case.eps, case.gate[:m])
+        per_tok = (time.perf_counter() - t0) / m
+        m = int(max(m, min(n, args.cpu_seconds / per_tok)))
+        t0 = time.perf_counter()
+        G.forward(case.x[:m], case.group_id[:m], case.gamma, case.beta, case.eps, case.gate[:m])
+        G.backward(case.dy[:m], case.x[:m], case.group_id[:m], case.gamma, case.beta, case.eps, case.gate[:m])
+        dt = time.perf_counter() - t0
+        result["cpu_baseline"] = {"value": m * (16 * d + 24) / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+                                  "sample": f"float64 NumPy oracle fwd+bwd on the first {m} of {n} tokens ({dt:.2f} s)",
+                                  "tokens_per_s": m / dt, "seconds": dt}
+    print(json.dumps(result), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
+    ap.add_argument("--op", default="hta", choices=["hta", "gln"],
+                    help="hta: the attention hot path (the headline metric); gln: the fused group layer normalization")
+    ap.add_argument("--groups", type=int, default=8, help="--op gln: number of normalization groups")
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
@@ -108,6 +211,8 @@ def main() -> int:
               "supported. Users are independent samples, so a multi-GPU run would be data parallel with no exchange.",
               file=sys.stderr)
         return 2
+    if args.op == "gln":
+        return bench_gln(args)
 
     import torch
     from paper_2602_11235_amd import hta, inputs

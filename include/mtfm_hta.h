@@ -180,7 +180,7 @@ enum { MTFM_HTA_KERNEL_FWD = 0,      /* forward attention kernel */
        MTFM_HTA_KERNEL_BWD_SELF = 1, /* dk/dv of the target tokens' own keys */
        MTFM_HTA_KERNEL_BWD_DQ = 2,   /* dq (row-stationary pass; the whole backward of the fp32 path) */
        MTFM_HTA_KERNEL_BWD_DKDV = 3, /* dk, dv of the history keys (key-stationary pass) */
-       MTFM_HTA_N_KERNELS = 4 };
+       MTFM_HTA_N_KERNELS = 7        /* kinds 4..6 belong to mtfm_gln.h */ };
 MTFM_HTA_API int mtfm_hta_timing_enable(int slots);
 MTFM_HTA_API int mtfm_hta_timing_read(int kernel, float* ms, int capacity);
 

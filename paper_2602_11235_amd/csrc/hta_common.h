@@ -57,6 +57,8 @@ hipError_t launch_bwd_fp32(const Params& p, hipStream_t s);
 hipError_t launch_fwd_bf16(const Params& p, hipStream_t s);
 hipError_t launch_bwd_bf16(const Params& p, hipStream_t s);
 bool bf16_supported(int32_t d, int32_t Hq, int32_t Hkv);
+// stores the calling thread's error message (what mtfm_hta_last_error() returns) and hands `code` back
+int report_error(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
 // event hooks around each kernel (no-ops unless timing was enabled through the C ABI); `kind` is one of the
 // MTFM_HTA_KERNEL_* values
 void timing_begin(int kind, hipStream_t s);
