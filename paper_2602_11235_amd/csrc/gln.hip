@@ -21,6 +21,7 @@ constexpr int MAX_BLOCKS = 512;   // workgroups of a launch, and shares of dgamm
 constexpr int CHUNK = 512;        // features a wave covers per pass: 64 lanes x 8
 constexpr int MAX_CHUNKS = 4;     // d_model <= 2048
 constexpr int MAX_TABLE = 8192;   // n_groups x padded row length, in floats
+constexpr int MAX_GROUPS = MAX_TABLE / CHUNK;
 constexpr int REDUCE_SLICES = 16, REDUCE_COLS = 64;
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -34,7 +35,7 @@ struct Args {
     float *mean, *rstd, *partials;
     int64_t n;
     int32_t d, n_groups, row;  // row = d rounded up to whole chunks: the stride of a group's row in LDS
-    int32_t span;              // backward: consecutive tokens a wave takes at a time, at most 64
+    int32_t span;              // backward: tokens a wave takes per pass, at most 64 (a workgroup: WAVES times that)
     float eps;
 };
 
@@ -45,7 +46,7 @@ struct Raw;
 template <>
 struct Raw<__bf16> {
     bf16x8 v;
-    __device__ void load(const __bf16* p) { v = *(const bf16x8*)p; }
+    __device__ void load(const __bf16* p) { v = __builtin_nontemporal_load((const bf16x8*)p); }
     __device__ float operator[](int j) const { return (float)v[j]; }
 };
 template <>
@@ -56,7 +57,7 @@ struct Raw<float> {
 };
 
 __device__ inline void load8(const __bf16* p, float (&f)[8]) {
-    const bf16x8 v = *(const bf16x8*)p;
+    const bf16x8 v = __builtin_nontemporal_load((const bf16x8*)p);
 #pragma unroll
     for (int j = 0; j < 8; j++) f[j] = (float)v[j];
 }
@@ -69,7 +70,7 @@ __device__ inline void store8(__bf16* p, const float (&f)[8]) {
     bf16x8 v;
 #pragma unroll
     for (int j = 0; j < 8; j++) v[j] = (__bf16)f[j];  // round to nearest even
-    *(bf16x8*)p = v;
+    __builtin_nontemporal_store(v, (bf16x8*)p);  // written once, not read again by this kernel
 }
 __device__ inline void store8(float* p, const float (&f)[8]) {
     floatx4 a, b;
@@ -217,8 +218,8 @@ __global__ __launch_bounds__(THREADS, CPL <= 2 ? 4 : 2) void fwd_kernel(const Ar
     }
 }
 
-// Backward.  A wave takes a span of up to 64 consecutive tokens (lane l holds the group of token l of the span)
-// and works through it group by group: the tokens of one group add their dz (.) xhat and dz into registers, and
+// Backward.  A wave takes up to 64 tokens at a time (lane l holds the group and position of the l-th of them)
+// and works through them group by group: the tokens of one group add their dz (.) xhat and dz into registers, and
 // only when the group is done do these go to the workgroup's accumulators in LDS -- a few atomic adds per span
 // instead of sixteen per token.
 template <typename T, int CPL, bool GATED>
@@ -243,12 +244,39 @@ __global__ __launch_bounds__(THREADS, CPL == 1 ? 4 : 2) void bwd_kernel(const Ar
     const T* ug = (const T*)a.gate;
     T* dxg = (T*)a.dx;
     T* dug = (T*)a.dgate;
-    const int64_t stride = (int64_t)gridDim.x * WAVES * a.span;
-    for (int64_t base = ((int64_t)blockIdx.x * WAVES + wave) * a.span; base < a.n; base += stride) {
-        int g_lane = -1;
-        if (lane < a.span && base + lane < a.n) {
-            const int g = a.group_id[base + lane];
-            g_lane = g < 0 ? 0 : (g >= a.n_groups ? a.n_groups - 1 : g);
+    // A workgroup takes a span of up to 512 consecutive tokens per pass and orders it by group (a counting sort of
+    // the ids in LDS); each wave then takes an equal share of the ordered span, so it meets only the few groups
+    // its share straddles, however skewed the group sizes are.
+    __shared__ int sorted_s[THREADS];           // (group << 16) | offset of the token in the span
+    __shared__ int counts_s[WAVES][MAX_GROUPS];  // tokens of each group among a wave's 64 candidates
+    const int block_span = a.span * WAVES;
+    for (int64_t base = (int64_t)blockIdx.x * block_span; base < a.n; base += (int64_t)gridDim.x * block_span) {
+        const int live = (int)(a.n - base < block_span ? a.n - base : block_span);
+        int g_me = -1;
+        if ((int)threadIdx.x < live) {
+            const int g = a.group_id[base + threadIdx.x];
+            g_me = g < 0 ? 0 : (g >= a.n_groups ? a.n_groups - 1 : g);
+        }
+        int rank = 0;
+        for (int g = 0; g < a.n_groups; g++) {
+            const uint64_t m = __ballot(g_me == g);
+            if (g_me == g) rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0));
+            if (lane == 0) counts_s[wave][g] = __builtin_popcountll(m);
+        }
+        __syncthreads();
+        if (g_me >= 0) {
+            int pos = rank;
+            for (int g = 0; g < g_me; g++)
+                for (int w = 0; w < WAVES; w++) pos += counts_s[w][g];
+            for (int w = 0; w < wave; w++) pos += counts_s[w][g_me];
+            sorted_s[pos] = (g_me << 16) | (int)threadIdx.x;
+        }
+        __syncthreads();
+        const int per_wave = (live + WAVES - 1) / WAVES;
+        int g_lane = -1, off_lane = 0;
+        if (lane < per_wave && wave * per_wave + lane < live) {
+            const int e = sorted_s[wave * per_wave + lane];
+            g_lane = e >> 16, off_lane = e & 0xFFFF;
         }
         uint64_t todo = __ballot(g_lane >= 0);
         while (todo) {
@@ -264,7 +292,7 @@ __global__ __launch_bounds__(THREADS, CPL == 1 ? 4 : 2) void bwd_kernel(const Ar
                 int64_t tok[TPW];
 #pragma unroll
                 for (int k = 0; k < TPW; k++) {
-                    tok[k] = members ? base + __builtin_ctzll(members) : -1;
+                    tok[k] = members ? base + __builtin_amdgcn_readlane(off_lane, __builtin_ctzll(members)) : -1;
                     members &= members - 1;  // stays 0 once empty
                 }
                 Raw<T> gv[TPW][CPL], xv[TPW][CPL], uv[TPW][CPL];
