@@ -93,6 +93,18 @@ def recorded_traffic(workload: str, kernel: str, family: str = "hta_fwd_bwd"):
     return None
 
 
+def calibration_copy(torch, mib: int) -> None:
+    """One plain device copy of `mib` MiB (known HBM traffic) for scaling the counters of a rocprofv3 --pmc run."""
+    if mib <= 0:
+        return
+    src = torch.ones(mib << 20, dtype=torch.uint8, device="cuda:0")
+    dst = torch.empty_like(src)
+    torch.cuda.synchronize()
+    dst.copy_(src)  # reads and writes exactly `mib` MiB
+    torch.cuda.synchronize()
+    del src, dst
+
+
 def bench_gln(args) -> int:
     """--op gln: one step = the gated fused group layer normalization, forward + backward, over all tokens of the
     headline batch at the model width of its heads (d_model = Hq * head_dim).  HBM-bound: the line reports GB/s of
@@ -128,6 +140,7 @@ def bench_gln(args) -> int:
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    calibration_copy(torch, args.calibration_copy_mib)
     hta.mtfm_hta_timing_enable(args.steps)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -248,13 +261,7 @@ def main() -> int:
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    if args.calibration_copy_mib > 0:
-        src = torch.ones(args.calibration_copy_mib << 20, dtype=torch.uint8, device="cuda:0")
-        dst = torch.empty_like(src)
-        torch.cuda.synchronize()
-        dst.copy_(src)  # reads and writes exactly calibration_copy_mib MiB
-        torch.cuda.synchronize()
-        del src, dst
+    calibration_copy(torch, args.calibration_copy_mib)
     hta.mtfm_hta_timing_enable(args.steps)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
