@@ -205,10 +205,100 @@ def bench_gln(args) -> int:
     return 0
 
 
+def bench_infer(args) -> int:
+    """--op infer: one step = one forward call of the target layer over a handful of requests (inference shape:
+    request-level aggregation, forward only).  The batch is far too small to fill the chip with (user, kv head) groups,
+    so the library splits the keys of each group over workgroups; the figure of merit is the latency of a call."""
+    import torch
+    from paper_2602_11235_amd import hta, inputs
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    hta.load_library()
+    cfg = inputs.CONFIGS[args.config if args.config.startswith("I") else "I2"]
+    case = inputs.make_case(cfg)
+
+    def dev(x):
+        t = torch.from_numpy(np.ascontiguousarray(x)).to("cuda:0")
+        return t.to(torch.bfloat16) if cfg.dtype == "bf16" and t.dtype == torch.float32 else t
+
+    rt = {}
+    if case.rt_len is not None:
+        rt = dict(rt_len=dev(case.rt_len), timestamps=dev(case.timestamps), max_rt=int(case.rt_len.max()))
+    batch = hta.Batch(dev(case.q), dev(case.k), dev(case.v), dev(case.q_offsets), dev(case.kv_offsets),
+                      dev(case.hist_len), dev(case.n_targets), int(case.hist_len.max()), int(case.n_targets.max()),
+                      case.scale, cfg.layer, **rt)
+    for _ in range(args.warmup):
+        batch.forward()
+    torch.cuda.synchronize()
+    calibration_copy(torch, args.calibration_copy_mib)
+    # latency of a single call: enqueue, then wait for the result
+    lat = []
+    for _ in range(args.steps):
+        t0 = time.perf_counter()
+        batch.forward()
+        torch.cuda.synchronize()
+        lat.append(time.perf_counter() - t0)
+    # back-to-back calls (the stream never drains): the timed region of the JSON line
+    hta.mtfm_hta_timing_enable(args.steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        batch.forward()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms = hta.mtfm_hta_timing_read(hta.KERNEL_FWD)
+    hta.mtfm_hta_timing_enable(0)
+
+    d = cfg.head_dim
+    pairs = inputs.visible_pairs_of(case)
+    ms_per_step = elapsed / args.steps * 1e3
+    avg = float(np.mean(ms))
+    flops = 4.0 * d * pairs
+    tflops = flops / (avg * 1e-3) / 1e12
+    # operands a call has to read at least once: Q rows, K and V rows, and the output it writes
+    io_bytes = 2 * (2 * case.total_q * cfg.Hq * d + 2 * case.total_kv * cfg.Hkv * d)
+    result = {
+        "metric": "HTA target-layer forward at inference shape (few requests): requests/s, latency per call",
+        "value": case.batch / (ms_per_step * 1e-3), "unit": "requests/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: B={cfg.batch} hist={cfg.hist}{'' if cfg.rt is None else f' realtime={cfg.rt}'} targets={cfg.targets} "
+                               f"Hq={cfg.Hq} Hkv={cfg.Hkv} head_dim={d} layer=target fwd only",
+                   "seed": cfg.seed, "visible_pairs": pairs, "total_tokens": case.total_kv},
+        "latency_us": {"median": float(np.median(lat) * 1e6), "min": float(np.min(lat) * 1e6),
+                       "note": "host enqueue + device + synchronize, one call at a time"},
+        "candidates_per_s": int(case.n_targets.sum()) / (ms_per_step * 1e-3),
+        "kernels": {"fwd": {"avg_ms": avg, "min_ms": float(np.min(ms)), "launches": len(ms), "tflops": tflops,
+                            "note": "split-key forward kernel + merge kernel (one event pair around both)"}},
+        "roofline": {"bound": "mfma", "kernel": "fwd", "achieved": tflops, "peak": BF16_MFMA_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": tflops / BF16_MFMA_PEAK_TFLOPS, "traffic": None,
+                     "avg_kernel_ms": avg, "algorithmic_flops_per_launch": flops,
+                     "note": f"latency-bound: a call has {flops / 1e9:.2f} GFLOP and {io_bytes / 1e6:.1f} MB of operands, "
+                             "microseconds of work for the whole chip; what is measured is the critical path of one call"},
+    }
+    if args.cpu_seconds > 0:
+        log("[bench] timing the float64 oracle on a bounded sample ...")
+        from oracle import hta_oracle as O
+        O.num_threads()
+        users = list(range(min(case.batch, 2)))
+        sub = inputs.take_users(case, users)
+        t0 = time.perf_counter()
+        O.forward(sub.q, sub.k, sub.v, sub.q_offsets, sub.kv_offsets, sub.hist_len, sub.n_targets, sub.scale,
+                  sub.cfg.layer, rt_len=sub.rt_len, timestamps=sub.timestamps)
+        dt = time.perf_counter() - t0
+        result["cpu_baseline"] = {"value": len(users) / dt, "unit": "requests/s", "cores": O.num_threads(),
+                                  "kind": "oracle", "seconds": dt,
+                                  "sample": f"float64 oracle forward on the first {len(users)} of {case.batch} requests of {cfg.name}"}
+    print(json.dumps(result), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
-    ap.add_argument("--op", default="hta", choices=["hta", "gln"],
-                    help="hta: the attention hot path (the headline metric); gln: the fused group layer normalization")
+    ap.add_argument("--op", default="hta", choices=["hta", "gln", "infer"],
+                    help="hta: the attention hot path (the headline metric); gln: the fused group layer normalization; "
+                         "infer: forward-only target layer on a few requests (--config I1 | I2 | I3 | I2_RT)")
     ap.add_argument("--groups", type=int, default=8, help="--op gln: number of normalization groups")
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
@@ -226,6 +316,8 @@ def main() -> int:
         return 2
     if args.op == "gln":
         return bench_gln(args)
+    if args.op == "infer":
+        return bench_infer(args)
 
     import torch
     from paper_2602_11235_amd import hta, inputs

@@ -69,6 +69,10 @@ enum { MTFM_HTA_LAYER_FULL = 0, MTFM_HTA_LAYER_TARGET = 1 };
  * counters of its persistent kernels and the user schedule (users ordered by decreasing number of
  * attention tiles, from hist_len / n_targets) -- and, for the backward pass, two float32 values per
  * (query head, query row): -delta = -<dout, out> and -lse / softmax_scale.
+ * A forward call on so few users that (user, kv head, row tile) items cannot give every compute unit a workgroup
+ * (a handful of requests at inference; decided from batch, the max_* bounds and the head shape alone) splits the keys
+ * of each item over several workgroups; the workspace then also holds their partial results, float32
+ * [splits][total_q][Hq][head_dim] and [splits][Hq][total_q], which a second kernel merges into out and lse.
  * is_bwd = 0 for mtfm_hta_fwd, 1 for mtfm_hta_bwd.  Returns (size_t)-1 for invalid arguments.
  * The workspace must be 256-byte aligned; its contents are undefined before and after a call and it
  * may be reused by the next call on the same stream.  Two calls that run at the same time (on

@@ -413,15 +413,18 @@ int grid_for(int64_t n_tokens, int tokens_per_wave) {
     return (int)(blocks < MAX_BLOCKS ? blocks : MAX_BLOCKS);
 }
 
+// Lets `kernel` use the whole 160 KB of LDS as dynamic shared memory.  Asked for once per kernel (the first call is
+// not a stream operation, so it is kept out of later calls that a caller may be capturing into a graph).
 template <typename KernelT>
-hipError_t allow_lds(KernelT kernel, size_t bytes) {
-    return hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+hipError_t allow_lds(KernelT kernel) {
+    static hipError_t state = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    return state;
 }
 
 template <typename T, int CPL, bool GATED>
 hipError_t launch_fwd_as(const Args& a, hipStream_t s) {
     const size_t lds = (size_t)2 * a.n_groups * a.row * sizeof(float);
-    hipError_t e = allow_lds(fwd_kernel<T, CPL, GATED>, lds);
+    hipError_t e = allow_lds(fwd_kernel<T, CPL, GATED>);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL((fwd_kernel<T, CPL, GATED>), dim3(grid_for(a.n, CPL == 1 ? 2 : 1)), dim3(THREADS), lds, s, a);
     return hipGetLastError();
@@ -430,7 +433,7 @@ hipError_t launch_fwd_as(const Args& a, hipStream_t s) {
 template <typename T, int CPL, bool GATED>
 hipError_t launch_bwd_as(const Args& a, hipStream_t s) {
     const size_t lds = (size_t)(GATED ? 4 : 3) * a.n_groups * a.row * sizeof(float);
-    hipError_t e = allow_lds(bwd_kernel<T, CPL, GATED>, lds);
+    hipError_t e = allow_lds(bwd_kernel<T, CPL, GATED>);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL((bwd_kernel<T, CPL, GATED>), dim3(grid_for(a.n, 1)), dim3(THREADS), lds, s, a);
     return hipGetLastError();

@@ -33,18 +33,31 @@ int report_error(int code, const char* fmt, ...) {
 
 namespace {
 
+// key splits of a forward call, from its host-known bounds (1: none)
+int forward_splits(int dtype, int layer, int32_t batch, int32_t max_hist, int32_t max_rt, int32_t max_targets, int32_t Hq,
+                   int32_t Hkv, int32_t d) {
+    if (dtype != MTFM_HTA_BF16) return 1;
+    const int64_t keys = (int64_t)max_hist + max_rt;
+    const int64_t rows = layer == MTFM_HTA_LAYER_FULL ? keys + max_targets : (int64_t)max_targets;
+    return hta::fwd_key_splits(batch, Hq, Hkv, d, rows, keys);
+}
+
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Workspace {
-    size_t order_off, delta_off, lse_off, lim_off, total;
+    size_t order_off, delta_off, lse_off, lim_off, opart_off, lsepart_off, total;
+    int splits;
 };
 
 // Layout of the caller's workspace (bf16 path; the fp32 debug path needs none):
 //   work counters (256 bytes) and order [batch] int32, users by decreasing tile count; both rebuilt by every call
 //   -delta and -lse/scale, [Hq][total_q] f32 each, the latter followed by one sentinel element   backward only
 //   with real-time tokens (both dtypes): lim [total_q] int32, the per-row limits of mask rule 2, rebuilt by every call
-Workspace plan_workspace(int dtype, int is_bwd, int32_t batch, int64_t total_q, int32_t Hq, bool has_rt) {
-    Workspace w{0, 0, 0, 0, 0};
+//   forward pass split over the keys (`splits` > 1: few requests, decided from the host-known bounds alone):
+//   partial outputs [splits][total_q][Hq][d] f32 and their logsumexps [splits][Hq][total_q] f32
+Workspace plan_workspace(int dtype, int is_bwd, int32_t batch, int64_t total_q, int32_t Hq, bool has_rt, int splits = 1,
+                         int32_t d = 0) {
+    Workspace w{0, 0, 0, 0, 0, 0, 0, 1};
     if (has_rt) {
         w.lim_off = 0;
         w.total = align256((size_t)total_q * sizeof(int32_t));
@@ -57,6 +70,12 @@ Workspace plan_workspace(int dtype, int is_bwd, int32_t batch, int64_t total_q, 
         w.total += align256((size_t)total_q * Hq * sizeof(float));
         w.lse_off = w.total;
         w.total += align256(((size_t)total_q * Hq + 1) * sizeof(float));
+    } else if (splits > 1) {
+        w.splits = splits;
+        w.opart_off = w.total;
+        w.total += align256((size_t)splits * total_q * Hq * d * sizeof(float));
+        w.lsepart_off = w.total;
+        w.total += align256((size_t)splits * total_q * Hq * sizeof(float));
     }
     return w;
 }
@@ -110,7 +129,8 @@ size_t mtfm_hta_workspace_bytes(int layer, int dtype, int is_bwd, int32_t batch,
                                 int32_t max_hist, int32_t max_targets, int32_t Hq, int32_t Hkv, int32_t head_dim) {
     if (check_scalars(layer, dtype, batch, total_q, total_kv, max_hist, 0, max_targets, Hq, Hkv, head_dim) != MTFM_HTA_OK)
         return (size_t)-1;
-    return plan_workspace(dtype, is_bwd, batch, total_q, Hq, false).total;
+    const int splits = is_bwd ? 1 : forward_splits(dtype, layer, batch, max_hist, 0, max_targets, Hq, Hkv, head_dim);
+    return plan_workspace(dtype, is_bwd, batch, total_q, Hq, false, splits, head_dim).total;
 }
 
 size_t mtfm_hta_workspace_bytes_rt(int layer, int dtype, int is_bwd, int32_t batch, int64_t total_q, int64_t total_kv,
@@ -118,7 +138,8 @@ size_t mtfm_hta_workspace_bytes_rt(int layer, int dtype, int is_bwd, int32_t bat
                                    int32_t head_dim) {
     if (check_scalars(layer, dtype, batch, total_q, total_kv, max_hist, max_rt, max_targets, Hq, Hkv, head_dim) != MTFM_HTA_OK)
         return (size_t)-1;
-    return plan_workspace(dtype, is_bwd, batch, total_q, Hq, true).total;
+    const int splits = is_bwd ? 1 : forward_splits(dtype, layer, batch, max_hist, max_rt, max_targets, Hq, Hkv, head_dim);
+    return plan_workspace(dtype, is_bwd, batch, total_q, Hq, true, splits, head_dim).total;
 }
 
 static int validate_host_impl(const int32_t* q_offsets, const int32_t* kv_offsets, const int32_t* hist_len,
@@ -186,7 +207,8 @@ static int fwd_impl(const void* q, const void* k, const void* v, void* out, floa
     if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out))
         return fail(MTFM_HTA_ERR_INVALID_ARG, "q, k, v, out must be 16-byte aligned");
     if (has_rt && !timestamps) return fail(MTFM_HTA_ERR_INVALID_ARG, "null pointer argument");
-    const Workspace w = plan_workspace(dtype, 0, batch, total_q, Hq, has_rt);
+    const int splits = forward_splits(dtype, layer, batch, max_hist, max_rt, max_targets, Hq, Hkv, head_dim);
+    const Workspace w = plan_workspace(dtype, 0, batch, total_q, Hq, has_rt, splits, head_dim);
     rc = check_workspace(w, workspace, workspace_bytes);
     if (rc != MTFM_HTA_OK) return rc;
     hta::Params p{};
@@ -202,10 +224,18 @@ static int fwd_impl(const void* q, const void* k, const void* v, void* out, floa
         e = hta::launch_rt_limits(p, s);
     }
     if (e == hipSuccess && dtype == MTFM_HTA_BF16) {
-        void* region = (char*)workspace + w.order_off;
-        e = hta::launch_schedule(p, region, s);
-        p.order = hta::schedule_order(region);
-        p.queue = hta::schedule_queue(region, 0);  // the launchers add the kernel kind
+        p.n_splits = w.splits;
+        if (w.splits <= 1) {
+            void* region = (char*)workspace + w.order_off;
+            e = hta::launch_schedule(p, region, s);
+            p.order = hta::schedule_order(region);
+            p.queue = hta::schedule_queue(region, 0);  // the launchers add the kernel kind
+        } else {
+            // a few users that do not fill the chip anyway: no long-first order (p.order stays null = as given),
+            // and one kernel less on the critical path of the call
+            p.o_part = (float*)((char*)workspace + w.opart_off);
+            p.lse_part = (float*)((char*)workspace + w.lsepart_off);
+        }
     }
     if (e == hipSuccess) e = dtype == MTFM_HTA_FP32 ? hta::launch_fwd_fp32(p, s) : hta::launch_fwd_bf16(p, s);
     if (e != hipSuccess) return fail(MTFM_HTA_ERR_LAUNCH, "forward launch failed: %s", hipGetErrorString(e));

@@ -39,6 +39,10 @@ struct Params {
     const int32_t* rt_len;  // [B] real-time tokens of each user, between its history and its target tokens
     const int32_t* ts;      // [total_kv] one timestamp per K/V row
     int32_t max_rt;
+    // forward pass split over the keys (few requests: inference); n_splits <= 1 = not split
+    int32_t n_splits;
+    float* o_part;          // [n_splits][total_q][Hq][d] partial outputs, each normalised by its own sum
+    float* lse_part;        // [n_splits][Hq][total_q]    logsumexp of each split's keys (-inf: none)
     int32_t* lim;           // [total_q] carved out of the workspace: number of leading K/V rows of the user (history, then
                             // the real-time tokens strictly earlier than the query) that the query row sees
 };
@@ -57,6 +61,8 @@ hipError_t launch_bwd_fp32(const Params& p, hipStream_t s);
 hipError_t launch_fwd_bf16(const Params& p, hipStream_t s);
 hipError_t launch_bwd_bf16(const Params& p, hipStream_t s);
 bool bf16_supported(int32_t d, int32_t Hq, int32_t Hkv);
+// number of key splits the bf16 forward pass uses for these host-known bounds (1 = none); decides the workspace too
+int fwd_key_splits(int32_t batch, int32_t Hq, int32_t Hkv, int32_t d, int64_t max_rows, int64_t max_keys);
 // stores the calling thread's error message (what mtfm_hta_last_error() returns) and hands `code` back
 int report_error(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
 // event hooks around each kernel (no-ops unless timing was enabled through the C ABI); `kind` is one of the

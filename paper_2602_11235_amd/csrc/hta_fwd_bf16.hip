@@ -30,7 +30,12 @@ constexpr float RESCALE_SLACK = 8.f;  // log2 units a row's logits may exceed it
 // the same tile loop; a sub-tile that reaches past the history is masked per query row with the row's limit
 // (p.lim: history + the real-time tokens strictly earlier than the row), and a real-time row gets its own key in the
 // epilogue exactly like a target row.
-template <int D, int RB, int NW, bool RT>
+//
+// SPLIT: the launch has too few (user, kv head, row tile) items to fill the chip (a handful of requests at
+// inference).  The grid gets a second dimension: workgroup (x, y) runs key tiles [y, y+1) * n_kt / n_splits of item x
+// and leaves a partial result -- its rows normalised by its own sum, in float32, with the logsumexp of its keys -- in
+// the workspace; split 0 also takes the rows' own keys.  merge_splits_kernel combines the partial results.
+template <int D, int RB, int NW, bool RT, bool SPLIT>
 __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb, int n_hc, int tpg) {
     using ST = KvStage<D, NW>;
     constexpr int NKS = D / 16, NDB = D / 32, NKB = BN / 32;
@@ -89,7 +94,10 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb,
             for (int v = 0; v < 16; v++) O[rb][db][v] = 0.f;
     }
 
-    const int n_kt = (LK + BN - 1) / BN;
+    const int n_kt_all = (LK + BN - 1) / BN;
+    const int split = SPLIT ? (int)blockIdx.y : 0;
+    const int t_lo = SPLIT ? split * n_kt_all / p.n_splits : 0;               // first key tile of this workgroup
+    const int n_kt = (SPLIT ? (split + 1) * n_kt_all / p.n_splits : n_kt_all) - t_lo;  // and how many it runs
     int nat[NKS], tlo[NDB], thi[NDB];  // per-lane element offsets of the operand fragments inside a swizzled tile
     natural_offsets<D>(nat, lane);
     transposed_offsets<D>(tlo, thi, lane);
@@ -187,23 +195,23 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb,
     // at the start of every workgroup.  From the wait on, the only vector-memory traffic of the loop are the
     // asynchronous copies, which this code counts itself; the compiler must not be left with pending loads of its own
     // (the Q fragments) that it would wait for inside the loop.
-    if (n_kt > 0) ST::issue(kg, vg, kv_base, p.Hkv, g, LK, 0, smem_addr, voff, wave_u, lane);
-    if (AHEAD > 1 && n_kt > 1) ST::issue(kg, vg, kv_base, p.Hkv, g, LK, 1, smem_addr + ST::BYTES, voff, wave_u, lane);
+    if (n_kt > 0) ST::issue(kg, vg, kv_base, p.Hkv, g, LK, t_lo, smem_addr, voff, wave_u, lane);
+    if (AHEAD > 1 && n_kt > 1) ST::issue(kg, vg, kv_base, p.Hkv, g, LK, t_lo + 1, smem_addr + ST::BYTES, voff, wave_u, lane);
     wait_vmem_loads();
     lds_barrier();
-    // Tile t is consumed from stage t % NSTAGE while tile t+AHEAD is fetched into stage (t+AHEAD) % NSTAGE, which was
+    // (t counts from this workgroup's first tile.)  Tile t is consumed from stage t % NSTAGE while tile t+AHEAD is fetched into stage (t+AHEAD) % NSTAGE, which was
     // last read for tile t-1, i.e. before the barrier that every wave has passed.
     auto tile = [&](int t, auto St) __attribute__((always_inline)) {
         constexpr int st = decltype(St)::value;
         if (t + AHEAD < n_kt)
-            ST::issue(kg, vg, kv_base, p.Hkv, g, LK, t + AHEAD, smem_addr + ((st + AHEAD) % NSTAGE) * ST::BYTES, voff, wave_u, lane);
+            ST::issue(kg, vg, kv_base, p.Hkv, g, LK, t_lo + t + AHEAD, smem_addr + ((st + AHEAD) % NSTAGE) * ST::BYTES, voff, wave_u, lane);
         const __bf16* Ks = (const __bf16*)(smem + st * ST::BYTES);
         const __bf16* Vs = Ks + ST::TILE;
-        const int live = LK - t * BN;  // keys of this tile that exist (>= 1)
+        const int live = LK - (t_lo + t) * BN;  // keys of this tile that exist (>= 1)
 #pragma unroll
         for (int kb = 0; kb < NKB; kb++) {
             const int n_live = live - kb * 32;
-            if (n_live > 0) subtile(Ks + kb * 32 * D, Vs + kb * 32 * D, n_live, t * BN + kb * 32);
+            if (n_live > 0) subtile(Ks + kb * 32 * D, Vs + kb * 32 * D, n_live, (t_lo + t) * BN + kb * 32);
         }
         // tile t+1 must have landed; a tile requested after it may stay in flight
         if (AHEAD > 1 && t + 2 < n_kt) wait_vmem_outstanding<ST::COPIES>(); else wait_vmem_outstanding<0>();
@@ -224,7 +232,7 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb,
         const int row = wrow0 + rb * 32 + l32;
         const bool live = row < n_rows;
         const int tok = tok_shift + row;
-        if (live && tok >= L) {
+        if (live && tok >= L && split == 0) {
             const int64_t off = ((kv_base + tok) * p.Hkv + g) * D;
             const __bf16* kp = kg + off + 8 * hf;
             float dot = 0.f;
@@ -251,7 +259,23 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb,
                 }
         }
         const float lt = l[rb] + other_half(l[rb]);
-        if (live) {
+        if (live && SPLIT) {
+            // partial result of this split: rows normalised by their own sum (0 when the split saw no key: lse = -inf)
+            const float inv = lt > 0.f ? 1.f / lt : 0.f;
+            float* op = p.o_part + (((int64_t)split * p.total_q + q_base + row) * p.Hq + h) * D;
+#pragma unroll
+            for (int db = 0; db < NDB; db++)
+#pragma unroll
+                for (int v4 = 0; v4 < 4; v4++) {
+                    floatx4 o4;
+#pragma unroll
+                    for (int j = 0; j < 4; j++) o4[j] = O[rb][db][4 * v4 + j] * inv;
+                    *(floatx4*)(op + db * 32 + 8 * v4 + 4 * hf) = o4;
+                }
+            if (hf == 0)
+                p.lse_part[((int64_t)split * p.Hq + h) * p.total_q + q_base + row] =
+                    lt > 0.f ? (m[rb] + __builtin_amdgcn_logf(lt)) * LN2 : -INFINITY;
+        } else if (live) {
             const float inv = 1.f / lt;
             __bf16* op = og + ((q_base + row) * p.Hq + h) * D;
 #pragma unroll
@@ -268,22 +292,86 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb,
     }
 }
 
+// out = sum_s w_s O_s / sum_s w_s with w_s = exp(lse_s - max lse), lse = max lse + log sum_s w_s: the exact
+// combination of softmax results over disjoint key sets.  One thread per 4 features of a (row, head).
+__global__ __launch_bounds__(256) void merge_splits_kernel(Params p) {
+    const int64_t quads = p.d / 4;
+    const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (id >= p.total_q * p.Hq * quads) return;
+    const int c = (int)(id % quads);
+    const int64_t rh = id / quads;
+    const int h = (int)(rh % p.Hq);
+    const int64_t row = rh / p.Hq;
+    // all loads of a thread are independent: issue them in batches of eight instead of one memory latency per split
+    const float* lp = p.lse_part + (int64_t)h * p.total_q + row;
+    const float* op = p.o_part + (row * p.Hq + h) * p.d + 4 * c;
+    const int64_t l_stride = (int64_t)p.Hq * p.total_q, o_stride = p.total_q * p.Hq * p.d;
+    float mx = -INFINITY;
+#pragma unroll 8
+    for (int s = 0; s < p.n_splits; s++) mx = fmaxf(mx, lp[s * l_stride]);
+    float sum = 0.f;
+    floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 8
+    for (int s = 0; s < p.n_splits; s++) {
+        const float w = __expf(lp[s * l_stride] - mx);
+        const floatx4 o = *(const floatx4*)(op + s * o_stride);
+        sum += w;
+        acc += w * o;
+    }
+    const float inv = 1.f / sum;
+    bf16x4 o4;
+#pragma unroll
+    for (int j = 0; j < 4; j++) o4[j] = (__bf16)(acc[j] * inv);
+    *(bf16x4*)((__bf16*)p.out + (row * p.Hq + h) * p.d + 4 * c) = o4;
+    if (c == 0) p.lse[(int64_t)h * p.total_q + row] = mx + __logf(sum);
+}
+
 int gcd(int a, int b) { return b == 0 ? a : gcd(b, a % b); }
+
+// launch geometry of the <D, RB, NW> kernel for a call's host-known bounds
+struct Geometry {
+    int hpb, n_hc;
+    int64_t n_rt, n_items;  // row tiles per (user, kv head, head chunk) group; groups x row tiles
+};
+Geometry geometry_of(int RB, int NW, int32_t batch, int32_t Hq, int32_t Hkv, int64_t max_rows) {
+    Geometry g;
+    const int r = Hq / Hkv;
+    g.hpb = gcd(r, NW);
+    g.n_hc = r / g.hpb;
+    const int BM = (NW / g.hpb) * RB * 32;
+    g.n_rt = (max_rows + BM - 1) / BM;
+    g.n_items = (int64_t)batch * Hkv * g.n_hc * g.n_rt;
+    return g;
+}
 
 template <int D, int RB, int NW>
 hipError_t launch(const Params& p, hipStream_t s) {
-    auto kernel = p.rt_len ? fwd_bf16_kernel<D, RB, NW, true> : fwd_bf16_kernel<D, RB, NW, false>;
-    const int r = p.Hq / p.Hkv;
-    const int hpb = gcd(r, NW);
-    const int n_hc = r / hpb;
-    const int BM = (NW / hpb) * RB * 32;
+    const bool split = p.n_splits > 1;
+    auto kernel = p.rt_len ? (split ? fwd_bf16_kernel<D, RB, NW, true, true> : fwd_bf16_kernel<D, RB, NW, true, false>)
+                           : (split ? fwd_bf16_kernel<D, RB, NW, false, true> : fwd_bf16_kernel<D, RB, NW, false, false>);
     const int64_t rows = max_query_rows(p);
     if (rows <= 0) return hipSuccess;
-    const int64_t n_rt = (rows + BM - 1) / BM;
-    const int64_t n_blocks = work_grid((int64_t)p.batch * p.Hkv * n_hc, n_rt);
+    const Geometry g = geometry_of(RB, NW, p.batch, p.Hq, p.Hkv, rows);
+    const int64_t n_blocks = work_grid((int64_t)p.batch * p.Hkv * g.n_hc, g.n_rt);
     if (n_blocks >= (1ll << 31)) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(kernel, dim3((unsigned)n_blocks), dim3(NW * 64), 0, s, p, hpb, n_hc, (int)n_rt);
-    return hipGetLastError();
+    hipLaunchKernelGGL(kernel, dim3((unsigned)n_blocks, split ? p.n_splits : 1), dim3(NW * 64), 0, s, p, g.hpb, g.n_hc,
+                       (int)g.n_rt);
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess && split) {
+        const int64_t threads = p.total_q * p.Hq * (p.d / 4);
+        hipLaunchKernelGGL(merge_splits_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, p);
+        e = hipGetLastError();
+    }
+    return e;
+}
+
+// (RB, NW) of the forward kernel for a head shape: eight waves of one 32-row block each whenever the head group fills
+// them (r a multiple of 4) -- the small register footprint lets four waves share a SIMD, which hides more latency than
+// a second row block per wave saves in LDS reads -- otherwise four waves with two row blocks each.
+void kernel_shape(int32_t d, int32_t Hq, int32_t Hkv, int& RB, int& NW) {
+    const bool wide = ((Hq / Hkv) % 4) == 0;
+    NW = wide ? 8 : 4;
+    RB = d == 32 ? 2 : (d == 64 ? (wide ? 1 : 2) : 1);
 }
 
 }  // namespace
@@ -294,12 +382,28 @@ bool bf16_supported(int32_t d, int32_t Hq, int32_t Hkv) {
     return d == 32 || d == 64 || d == 128;
 }
 
+// Key splits of the forward pass: 1 (none) when the (user, kv head, row tile) items already give every compute unit
+// a workgroup; otherwise enough splits for one workgroup per compute unit, each keeping at least MIN_TILES key tiles
+// (measured on 1..8 requests with 2k..8k histories: two workgroups per unit or shorter splits only add partial
+// results for the merge to read; fewer splits leave units idle).
+int fwd_key_splits(int32_t batch, int32_t Hq, int32_t Hkv, int32_t d, int64_t max_rows, int64_t max_keys) {
+    constexpr int64_t CUS = 256, MIN_TILES = 4, MAX_SPLITS = 32;
+    if (batch <= 0 || max_rows <= 0 || !bf16_supported(d, Hq, Hkv)) return 1;
+    int RB, NW;
+    kernel_shape(d, Hq, Hkv, RB, NW);
+    const Geometry g = geometry_of(RB, NW, batch, Hq, Hkv, max_rows);
+    if (g.n_items >= CUS) return 1;
+    const int64_t want = (CUS + g.n_items - 1) / g.n_items;
+    const int64_t by_len = ((max_keys + BN - 1) / BN) / MIN_TILES;
+    int64_t n = want < by_len ? want : by_len;
+    n = n < MAX_SPLITS ? n : MAX_SPLITS;
+    return n > 1 ? (int)n : 1;
+}
+
 hipError_t launch_fwd_bf16(const Params& p, hipStream_t s) {
-    // Eight waves of one 32-row block each whenever the head group fills them (r a multiple of 4): the small
-    // register footprint lets four waves share a SIMD, which hides more latency than a second row block per
-    // wave saves in LDS reads.  Otherwise four waves with two row blocks each.
-    const int r = p.Hq / p.Hkv;
-    const bool wide = (r % 4) == 0;
+    int RB, NW;
+    kernel_shape(p.d, p.Hq, p.Hkv, RB, NW);
+    const bool wide = NW == 8;
     hipError_t e;
     timing_begin(MTFM_HTA_KERNEL_FWD, s);
     switch (p.d) {

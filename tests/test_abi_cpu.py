@@ -27,9 +27,16 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_workspace_bytes_is_host_arithmetic():
-    # forward: the work counters (256 bytes) and the user order (4 users -> one 256-byte block)
-    assert hta.mtfm_hta_workspace_bytes(hta.LAYER_FULL, hta.BF16, False, 4, 1000, 1000, 512, 64, 8, 2, 64) == 512
+    # forward of a batch that fills the chip (300 users x 2 kv heads x row tiles): the work counters (256 bytes) and
+    # the user order (300 users -> 1280 bytes)
+    assert hta.mtfm_hta_workspace_bytes(hta.LAYER_FULL, hta.BF16, False, 300, 100000, 100000, 512, 64, 8, 2, 64) == 256 + 1280
     assert hta.mtfm_hta_workspace_bytes(hta.LAYER_FULL, hta.FP32, False, 4, 1000, 1000, 512, 64, 8, 2, 64) == 0
+    # forward of a few users: 4 users x 2 kv heads x 9 row tiles of 64 = 72 items for 256 compute units, so the keys
+    # are split (8 tiles of history, at least 4 per split -> 2 splits) and the partial results live in the workspace
+    few = hta.mtfm_hta_workspace_bytes(hta.LAYER_FULL, hta.BF16, False, 4, 1000, 1000, 512, 64, 8, 2, 64)
+    assert few == 512 + 2 * 1000 * 8 * 64 * 4 + 2 * 1000 * 8 * 4
+    # a history of fewer than eight tiles is not split
+    assert hta.mtfm_hta_workspace_bytes(hta.LAYER_TARGET, hta.BF16, False, 1, 16, 400, 384, 16, 8, 2, 64) == 512
     n = hta.mtfm_hta_workspace_bytes(hta.LAYER_FULL, hta.BF16, True, 4, 1000, 1000, 512, 64, 8, 2, 64)
     # backward: two float rows per (head, query row) on top of that, one of them with a sentinel element
     assert n >= 512 + 2 * 1000 * 8 * 4 and n % 256 == 0
