@@ -239,6 +239,17 @@ def bench_infer(args) -> int:
         batch.forward()
         torch.cuda.synchronize()
         lat.append(time.perf_counter() - t0)
+    # the same call replayed from a HIP graph (the library only enqueues kernels, so a caller can capture it)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        batch.forward()
+    torch.cuda.synchronize()
+    glat = []
+    for _ in range(args.steps):
+        t0 = time.perf_counter()
+        graph.replay()
+        torch.cuda.synchronize()
+        glat.append(time.perf_counter() - t0)
     # back-to-back calls (the stream never drains): the timed region of the JSON line
     hta.mtfm_hta_timing_enable(args.steps)
     torch.cuda.synchronize()
@@ -267,7 +278,8 @@ def bench_infer(args) -> int:
                                f"Hq={cfg.Hq} Hkv={cfg.Hkv} head_dim={d} layer=target fwd only",
                    "seed": cfg.seed, "visible_pairs": pairs, "total_tokens": case.total_kv},
         "latency_us": {"median": float(np.median(lat) * 1e6), "min": float(np.min(lat) * 1e6),
-                       "note": "host enqueue + device + synchronize, one call at a time"},
+                       "note": "host enqueue + device + synchronize, one call at a time",
+                       "graph_replay_median": float(np.median(glat) * 1e6), "graph_replay_min": float(np.min(glat) * 1e6)},
         "candidates_per_s": int(case.n_targets.sum()) / (ms_per_step * 1e-3),
         "kernels": {"fwd": {"avg_ms": avg, "min_ms": float(np.min(ms)), "launches": len(ms), "tflops": tflops,
                             "note": "split-key forward kernel + merge kernel (one event pair around both)"}},

@@ -145,7 +145,7 @@ CONFIGS: Dict[str, Config] = {
                     rt=("uniform", 32, 128)),
     "C4_RT": Config("C4_RT", LAYER_TARGET, 128, ("fixed", 2048), ("fixed", 128), 16, 4, 64, "bf16", 0.3, 13,
                     rt=("uniform", 32, 128)),
-    # Inference shapes (request-level aggregation, Section 3.1: one request = one user's history and the candidates of a
+    # Inference shapes (request-level aggregation, Section 3.1, and the serving set-up of Section 3.3.3: one request = one user's history and the candidates of a
     # scenario; forward only, target layer; the history K/V are shared by all candidates of the request).  A few
     # requests at a time: far fewer (user, kv head) groups than compute units.
     "I1": Config("I1", LAYER_TARGET, 1, ("fixed", 2048), ("fixed", 128), 8, 2, 64, "bf16", 0.3, 21),
