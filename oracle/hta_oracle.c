@@ -22,6 +22,13 @@
  *   - rule 2: "later" is strict (key timestamp < query timestamp), for every kind of query token; in
  *     addition a real-time token sees itself, like a target token does, so that no row is empty.
  *
+ *
+ * The other reading of phi2 (the layers are described as HSTU layers, whose attention weights are a pointwise,
+ * non-normalised nonlinearity): the hta_oracle_pw_* functions at the end of this file compute
+ *   out_i = norm * sum_{j visible to i} silu(scale <q_i, k_j>) v_j,   silu(x) = x / (1 + exp(-x)),
+ * with the same mask, heads and layers, and an explicit scalar `norm` (HSTU divides by the sequence length: the
+ * caller passes its reciprocal).  No row statistics exist in this reading.
+ *
  * Layout: q/out/dout/dq are [total_q][Hq][d]; k/v/dk/dv are [total_kv][Hkv][d]; lse is [Hq][total_q].
  * Per user b the K/V rows are L_b history tokens, then R_b real-time tokens, then T_b target tokens
  * (X = (H; R; T), Section 3.2.1), starting at kv_start[b]; ts[] holds one timestamp per K/V row.
@@ -253,4 +260,107 @@ int hta_oracle_probs(const double* q, const double* k, double* probs, int32_t q_
                      double scale, int32_t layer) {
     return hta_oracle_probs_rt(q, k, probs, q_start, kv_start, hist_len, 0, n_targets, NULL, head, Hq, Hkv, d, scale,
                                layer);
+}
+
+
+/* ---------------------------------------------------------------------------------------------------------------
+ * Pointwise reading of phi2: out_i = norm * sum_{j visible to i} silu(scale <q_i, k_j>) v_j.
+ * rt_len and ts may both be NULL.  Returns 0, or -1 on bad scalar arguments. */
+static double silu(double x) { return x / (1.0 + exp(-x)); }
+/* d silu / dx = sigma (1 + x (1 - sigma)) */
+static double silu_prime(double x) {
+    const double sg = 1.0 / (1.0 + exp(-x));
+    return sg * (1.0 + x * (1.0 - sg));
+}
+
+int hta_oracle_pw_fwd_rt(const double* q, const double* k, const double* v, double* out, const int32_t* q_start,
+                         const int32_t* kv_start, const int32_t* hist_len, const int32_t* rt_len,
+                         const int32_t* n_targets, const int32_t* ts, int32_t batch, int32_t Hq, int32_t Hkv, int32_t d,
+                         double scale, double norm, int32_t layer) {
+    if (Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0 || d <= 0 || batch < 0) return -1;
+    if (layer != LAYER_FULL && layer != LAYER_TARGET) return -1;
+    if (rt_len && !ts) return -1;
+    const int r = Hq / Hkv;
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int b = 0; b < batch; b++) {
+        for (int h = 0; h < Hq; h++) {
+            const int g = h / r;
+            const sample_t u = sample_of(b, kv_start, hist_len, rt_len, n_targets, ts);
+            const int64_t N = u.hist_len + u.rt_len + u.n_targets;
+            const int64_t first_tok = (layer == LAYER_FULL) ? 0 : u.hist_len + u.rt_len;
+            for (int64_t row = 0; row < N - first_tok; row++) {
+                const int64_t i = first_tok + row;
+                const double* qi = q + ((int64_t)(q_start[b] + row) * Hq + h) * d;
+                double* oi = out + ((int64_t)(q_start[b] + row) * Hq + h) * d;
+                for (int c = 0; c < d; c++) oi[c] = 0.0;
+                for (int64_t j = 0; j < N; j++) {
+                    if (!visible(i, j, &u)) continue;
+                    const double* kj = k + ((int64_t)(kv_start[b] + j) * Hkv + g) * d;
+                    const double* vj = v + ((int64_t)(kv_start[b] + j) * Hkv + g) * d;
+                    double dot = 0.0;
+                    for (int c = 0; c < d; c++) dot += qi[c] * kj[c];
+                    const double a = norm * silu(scale * dot);
+                    for (int c = 0; c < d; c++) oi[c] += a * vj[c];
+                }
+            }
+        }
+    }
+    return 0;
+}
+
+/*
+ * Backward of the pointwise forward:  x_ij = scale <q_i, k_j>,  a_ij = norm silu(x_ij)
+ *   dv_j = sum_{h in g} sum_i a_ij dout_i            da_ij = <dout_i, v_j>
+ *   dx_ij = norm da_ij silu'(x_ij)                   dq_i = scale sum_j dx_ij k_j     dk_j = scale sum_{h in g} sum_i dx_ij q_i
+ */
+int hta_oracle_pw_bwd_rt(const double* dout, const double* q, const double* k, const double* v, double* dq, double* dk,
+                         double* dv, const int32_t* q_start, const int32_t* kv_start, const int32_t* hist_len,
+                         const int32_t* rt_len, const int32_t* n_targets, const int32_t* ts, int32_t batch, int32_t Hq,
+                         int32_t Hkv, int32_t d, double scale, double norm, int32_t layer) {
+    if (Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0 || d <= 0 || batch < 0) return -1;
+    if (layer != LAYER_FULL && layer != LAYER_TARGET) return -1;
+    if (rt_len && !ts) return -1;
+    const int r = Hq / Hkv;
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int b = 0; b < batch; b++) {
+        for (int g = 0; g < Hkv; g++) { /* one thread owns all of dk/dv[b, :, g, :] */
+            const sample_t u = sample_of(b, kv_start, hist_len, rt_len, n_targets, ts);
+            const int64_t N = u.hist_len + u.rt_len + u.n_targets;
+            const int64_t first_tok = (layer == LAYER_FULL) ? 0 : u.hist_len + u.rt_len;
+            for (int64_t j = 0; j < N; j++) {
+                double* dkj = dk + ((int64_t)(kv_start[b] + j) * Hkv + g) * d;
+                double* dvj = dv + ((int64_t)(kv_start[b] + j) * Hkv + g) * d;
+                for (int c = 0; c < d; c++) dkj[c] = dvj[c] = 0.0;
+            }
+            for (int h = g * r; h < (g + 1) * r; h++) {
+                for (int64_t row = 0; row < N - first_tok; row++) {
+                    const int64_t i = first_tok + row;
+                    const int64_t qrow = (int64_t)(q_start[b] + row) * Hq + h;
+                    const double* qi = q + qrow * d;
+                    const double* doi = dout + qrow * d;
+                    double* dqi = dq + qrow * d;
+                    for (int c = 0; c < d; c++) dqi[c] = 0.0;
+                    for (int64_t j = 0; j < N; j++) {
+                        if (!visible(i, j, &u)) continue;
+                        const int64_t kvrow = (int64_t)(kv_start[b] + j) * Hkv + g;
+                        const double* kj = k + kvrow * d;
+                        const double* vj = v + kvrow * d;
+                        double dot = 0.0, da = 0.0;
+                        for (int c = 0; c < d; c++) { dot += qi[c] * kj[c]; da += doi[c] * vj[c]; }
+                        const double x = scale * dot;
+                        const double a = norm * silu(x);
+                        const double dx = norm * da * silu_prime(x);
+                        double* dkj = dk + kvrow * d;
+                        double* dvj = dv + kvrow * d;
+                        for (int c = 0; c < d; c++) {
+                            dqi[c] += scale * dx * kj[c];
+                            dkj[c] += scale * dx * qi[c];
+                            dvj[c] += a * doi[c];
+                        }
+                    }
+                }
+            }
+        }
+    }
+    return 0;
 }

@@ -48,6 +48,14 @@ def _load():
         lib.hta_oracle_probs_rt.restype = ctypes.c_int
         lib.hta_oracle_probs_rt.argtypes = ([dp, dp, dp] + [ctypes.c_int32] * 5 + [ip] + [ctypes.c_int32] * 4 +
                                             [ctypes.c_double, ctypes.c_int32])
+        lib.hta_oracle_pw_fwd_rt.restype = ctypes.c_int
+        lib.hta_oracle_pw_fwd_rt.argtypes = [dp, dp, dp, dp, ip, ip, ip, ip, ip, ip, ctypes.c_int32, ctypes.c_int32,
+                                             ctypes.c_int32, ctypes.c_int32, ctypes.c_double, ctypes.c_double,
+                                             ctypes.c_int32]
+        lib.hta_oracle_pw_bwd_rt.restype = ctypes.c_int
+        lib.hta_oracle_pw_bwd_rt.argtypes = [dp] * 7 + [ip, ip, ip, ip, ip, ip, ctypes.c_int32, ctypes.c_int32,
+                                                        ctypes.c_int32, ctypes.c_int32, ctypes.c_double, ctypes.c_double,
+                                                        ctypes.c_int32]
         lib.hta_oracle_num_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -155,3 +163,42 @@ def probs(q, k, q_start, kv_start, hist_len, n_targets, head, scale, layer, rt_l
     if rc != 0:
         raise ValueError("hta_oracle_probs: invalid arguments")
     return p
+
+
+def _ip_or_null(a):
+    return _ip(a) if a is not None else None
+
+
+def forward_pointwise(q, k, v, q_offsets, kv_offsets, hist_len, n_targets, scale, norm, layer, rt_len=None,
+                      timestamps=None):
+    """The pointwise reading of phi2: out_i = norm * sum over visible j of silu(scale <q_i, k_j>) v_j, float64."""
+    q, k, v = _f64(q), _f64(k), _f64(v)
+    qs, ks, hl, nt = _i32(q_offsets), _i32(kv_offsets), _i32(hist_len), _i32(n_targets)
+    rl = _i32(rt_len) if rt_len is not None else None
+    ts = _i32(timestamps) if timestamps is not None else None
+    _check_shapes(q, k, v, qs, ks, hl, nt, layer, rl, ts)
+    out = np.zeros_like(q)
+    rc = _load().hta_oracle_pw_fwd_rt(_dp(q), _dp(k), _dp(v), _dp(out), _ip(qs), _ip(ks), _ip(hl), _ip_or_null(rl),
+                                      _ip(nt), _ip_or_null(ts), hl.shape[0], q.shape[1], k.shape[1], q.shape[2],
+                                      float(scale), float(norm), int(layer))
+    if rc != 0:
+        raise ValueError("hta_oracle_pw_fwd: invalid arguments")
+    return out
+
+
+def backward_pointwise(dout, q, k, v, q_offsets, kv_offsets, hist_len, n_targets, scale, norm, layer, rt_len=None,
+                       timestamps=None):
+    """Returns (dq, dk, dv) of forward_pointwise for the upstream gradient ``dout``, float64."""
+    dout, q, k, v = _f64(dout), _f64(q), _f64(k), _f64(v)
+    qs, ks, hl, nt = _i32(q_offsets), _i32(kv_offsets), _i32(hist_len), _i32(n_targets)
+    rl = _i32(rt_len) if rt_len is not None else None
+    ts = _i32(timestamps) if timestamps is not None else None
+    _check_shapes(q, k, v, qs, ks, hl, nt, layer, rl, ts)
+    assert dout.shape == q.shape
+    dq, dk, dv = np.zeros_like(q), np.zeros_like(k), np.zeros_like(v)
+    rc = _load().hta_oracle_pw_bwd_rt(_dp(dout), _dp(q), _dp(k), _dp(v), _dp(dq), _dp(dk), _dp(dv), _ip(qs), _ip(ks),
+                                      _ip(hl), _ip_or_null(rl), _ip(nt), _ip_or_null(ts), hl.shape[0], q.shape[1],
+                                      k.shape[1], q.shape[2], float(scale), float(norm), int(layer))
+    if rc != 0:
+        raise ValueError("hta_oracle_pw_bwd: invalid arguments")
+    return dq, dk, dv
