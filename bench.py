@@ -41,7 +41,7 @@ def history_pairs(case, inputs) -> int:
     return int(case.cfg.Hq * (rows * L).sum())
 
 
-def cpu_baseline(case, inputs, budget_s: float):
+def cpu_baseline(case, inputs, budget_s: float, pointwise: bool = False):
     """Time the float64 oracle (forward + backward) on the first users of the batch: a probe on 2 users
     sizes the sample so that the run takes about `budget_s` seconds."""
     from oracle import hta_oracle as O
@@ -50,10 +50,16 @@ def cpu_baseline(case, inputs, budget_s: float):
         sub = inputs.take_users(case, users)
         t0 = time.perf_counter()
         rt = dict(rt_len=sub.rt_len, timestamps=sub.timestamps)
-        out, lse = O.forward(sub.q, sub.k, sub.v, sub.q_offsets, sub.kv_offsets, sub.hist_len, sub.n_targets,
-                             sub.scale, sub.cfg.layer, **rt)
-        O.backward(sub.dout, sub.q, sub.k, sub.v, out, lse, sub.q_offsets, sub.kv_offsets, sub.hist_len,
-                   sub.n_targets, sub.scale, sub.cfg.layer, **rt)
+        if pointwise:
+            O.forward_pointwise(sub.q, sub.k, sub.v, sub.q_offsets, sub.kv_offsets, sub.hist_len, sub.n_targets,
+                                sub.scale, 1e-3, sub.cfg.layer, **rt)
+            O.backward_pointwise(sub.dout, sub.q, sub.k, sub.v, sub.q_offsets, sub.kv_offsets, sub.hist_len,
+                                 sub.n_targets, sub.scale, 1e-3, sub.cfg.layer, **rt)
+        else:
+            out, lse = O.forward(sub.q, sub.k, sub.v, sub.q_offsets, sub.kv_offsets, sub.hist_len, sub.n_targets,
+                                 sub.scale, sub.cfg.layer, **rt)
+            O.backward(sub.dout, sub.q, sub.k, sub.v, out, lse, sub.q_offsets, sub.kv_offsets, sub.hist_len,
+                       sub.n_targets, sub.scale, sub.cfg.layer, **rt)
         dt = time.perf_counter() - t0
         pairs = inputs.visible_pairs_of(sub)
         return dt, pairs, sub.batch
@@ -308,8 +314,9 @@ def bench_infer(args) -> int:
 
 def main() -> int:
     ap = argparse.ArgumentParser()
-    ap.add_argument("--op", default="hta", choices=["hta", "gln", "infer"],
-                    help="hta: the attention hot path (the headline metric); gln: the fused group layer normalization; "
+    ap.add_argument("--op", default="hta", choices=["hta", "pointwise", "gln", "infer"],
+                    help="hta: the attention hot path (the headline metric); pointwise: the same path with the "
+                         "pointwise (SiLU) reading of phi2; gln: the fused group layer normalization; "
                          "infer: forward-only target layer on a few requests (--config I1 | I2 | I3 | I2_RT)")
     ap.add_argument("--groups", type=int, default=8, help="--op gln: number of normalization groups")
     ap.add_argument("--gpus", type=int, default=1)
@@ -332,11 +339,12 @@ def main() -> int:
         return bench_infer(args)
 
     import torch
-    from paper_2602_11235_amd import hta, inputs
+    from paper_2602_11235_amd import hta, hta_pw, inputs
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     hta.load_library()  # fail loudly if the HIP library is missing
+    pointwise = args.op == "pointwise"
 
     cfg = inputs.CONFIGS[args.config]
     t0 = time.perf_counter()
@@ -351,9 +359,16 @@ def main() -> int:
     rt = {}
     if case.rt_len is not None:  # samples with real-time tokens: the *_rt entry points
         rt = dict(rt_len=dev(case.rt_len), timestamps=dev(case.timestamps), max_rt=int(case.rt_len.max()))
-    batch = hta.Batch(dev(case.q), dev(case.k), dev(case.v), dev(case.q_offsets), dev(case.kv_offsets),
-                      dev(case.hist_len), dev(case.n_targets), int(case.hist_len.max()), int(case.n_targets.max()),
-                      case.scale, cfg.layer, **rt)
+    if pointwise:  # weights norm * silu(scale s); norm = 1 / longest sample, as HSTU divides by the sequence length
+        assert case.rt_len is None, "the pointwise variant takes samples of history + target tokens"
+        pw_norm = 1.0 / float((case.hist_len + case.n_targets).max())
+        batch = hta_pw.PointwiseBatch(dev(case.q), dev(case.k), dev(case.v), dev(case.q_offsets), dev(case.kv_offsets),
+                                      dev(case.hist_len), dev(case.n_targets), int(case.hist_len.max()),
+                                      int(case.n_targets.max()), case.scale, pw_norm, cfg.layer)
+    else:
+        batch = hta.Batch(dev(case.q), dev(case.k), dev(case.v), dev(case.q_offsets), dev(case.kv_offsets),
+                          dev(case.hist_len), dev(case.n_targets), int(case.hist_len.max()), int(case.n_targets.max()),
+                          case.scale, cfg.layer, **rt)
     dout = dev(case.dout)
     batch.prepare_backward()
     torch.cuda.synchronize()
@@ -406,7 +421,7 @@ def main() -> int:
                     "unit": "TFLOP/s", "frac": ach / BF16_MFMA_PEAK_TFLOPS, "traffic": None,
                     "avg_kernel_ms": kernels[dominant]["avg_ms"],
                     "algorithmic_flops_per_launch": flops[dominant]}
-        measured = recorded_traffic(cfg.name, dominant)
+        measured = None if pointwise else recorded_traffic(cfg.name, dominant)
         if measured is not None:
             roofline["traffic"] = measured["read_bytes"] + measured["write_bytes"]
             roofline["traffic_note"] = (f"HBM bytes per launch (read {measured['read_bytes']}, written "
@@ -414,7 +429,8 @@ def main() -> int:
                                         f"{measured['source']}; not measured by this run")
 
     result = {
-        "metric": "HTA fwd+bwd TFLOP/s & samples/s at B=256,L=1024,T=64; % of bf16 MFMA peak",
+        "metric": ("HTA fwd+bwd TFLOP/s & samples/s at B=256,L=1024,T=64; % of bf16 MFMA peak" if not pointwise else
+                   "HTA with pointwise (SiLU) weights, fwd+bwd TFLOP/s & samples/s; % of bf16 MFMA peak"),
         "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
@@ -429,7 +445,7 @@ def main() -> int:
     }
     if args.cpu_seconds > 0:
         log("[bench] timing the float64 oracle on a bounded sample ...")
-        result["cpu_baseline"] = cpu_baseline(case, inputs, args.cpu_seconds)
+        result["cpu_baseline"] = cpu_baseline(case, inputs, args.cpu_seconds, pointwise)
     print(json.dumps(result), flush=True)
     return 0
 

@@ -1,6 +1,7 @@
 // C ABI of libmtfm_hta.so: host-side argument checks and kernel dispatch.  No allocation, no
 // host<->device copies, no synchronisation here.
 #include "../../include/mtfm_hta.h"
+#include "../../include/mtfm_hta_pw.h"
 #include "hta_common.h"
 
 #include <cmath>
@@ -195,19 +196,22 @@ static int fwd_impl(const void* q, const void* k, const void* v, void* out, floa
                     const int32_t* kv_offsets, const int32_t* hist_len, const int32_t* rt_len, const int32_t* n_targets,
                     const int32_t* timestamps, int32_t batch, int64_t total_q, int64_t total_kv, int32_t max_hist,
                     int32_t max_rt, int32_t max_targets, int32_t Hq, int32_t Hkv, int32_t head_dim, float softmax_scale,
-                    int dtype, int layer, void* workspace, size_t workspace_bytes, void* stream) {
+                    int dtype, int layer, void* workspace, size_t workspace_bytes, void* stream, bool pointwise = false,
+                    float norm = 1.f) {
     const bool has_rt = rt_len != nullptr;
     int rc = check_scalars(layer, dtype, batch, total_q, total_kv, max_hist, max_rt, max_targets, Hq, Hkv, head_dim);
     if (rc != MTFM_HTA_OK) return rc;
     if (!(softmax_scale > 0.f) || !std::isfinite(softmax_scale))
-        return fail(MTFM_HTA_ERR_INVALID_ARG, "softmax_scale must be positive and finite");
+        return fail(MTFM_HTA_ERR_INVALID_ARG, "%s must be positive and finite", pointwise ? "scale" : "softmax_scale");
+    if (pointwise && (!(norm > 0.f) || !std::isfinite(norm)))
+        return fail(MTFM_HTA_ERR_INVALID_ARG, "norm must be positive and finite");
     if (batch == 0 || total_q == 0) return MTFM_HTA_OK;
-    if (!q || !k || !v || !out || !lse || !q_offsets || !kv_offsets || !hist_len || !n_targets)
+    if (!q || !k || !v || !out || (!lse && !pointwise) || !q_offsets || !kv_offsets || !hist_len || !n_targets)
         return fail(MTFM_HTA_ERR_INVALID_ARG, "null pointer argument");
     if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out))
         return fail(MTFM_HTA_ERR_INVALID_ARG, "q, k, v, out must be 16-byte aligned");
     if (has_rt && !timestamps) return fail(MTFM_HTA_ERR_INVALID_ARG, "null pointer argument");
-    const int splits = forward_splits(dtype, layer, batch, max_hist, max_rt, max_targets, Hq, Hkv, head_dim);
+    const int splits = pointwise ? 1 : forward_splits(dtype, layer, batch, max_hist, max_rt, max_targets, Hq, Hkv, head_dim);
     const Workspace w = plan_workspace(dtype, 0, batch, total_q, Hq, has_rt, splits, head_dim);
     rc = check_workspace(w, workspace, workspace_bytes);
     if (rc != MTFM_HTA_OK) return rc;
@@ -217,6 +221,7 @@ static int fwd_impl(const void* q, const void* k, const void* v, void* out, floa
     p.batch = batch; p.total_q = total_q; p.total_kv = total_kv; p.max_hist = max_hist; p.max_targets = max_targets;
     p.Hq = Hq; p.Hkv = Hkv; p.d = head_dim; p.scale = softmax_scale; p.layer = layer;
     p.rt_len = rt_len; p.ts = timestamps; p.max_rt = max_rt;
+    p.pointwise = pointwise ? 1 : 0; p.norm = norm;
     hipStream_t s = (hipStream_t)stream;
     hipError_t e = hipSuccess;
     if (has_rt) {
@@ -268,14 +273,18 @@ static int bwd_impl(const void* dout, const void* q, const void* k, const void* 
                     const int32_t* hist_len, const int32_t* rt_len, const int32_t* n_targets, const int32_t* timestamps,
                     int32_t batch, int64_t total_q, int64_t total_kv, int32_t max_hist, int32_t max_rt,
                     int32_t max_targets, int32_t Hq, int32_t Hkv, int32_t head_dim, float softmax_scale, int dtype,
-                    int layer, void* workspace, size_t workspace_bytes, void* stream) {
+                    int layer, void* workspace, size_t workspace_bytes, void* stream, bool pointwise = false,
+                    float norm = 1.f) {
     const bool has_rt = rt_len != nullptr;
     int rc = check_scalars(layer, dtype, batch, total_q, total_kv, max_hist, max_rt, max_targets, Hq, Hkv, head_dim);
     if (rc != MTFM_HTA_OK) return rc;
     if (!(softmax_scale > 0.f) || !std::isfinite(softmax_scale))
-        return fail(MTFM_HTA_ERR_INVALID_ARG, "softmax_scale must be positive and finite");
+        return fail(MTFM_HTA_ERR_INVALID_ARG, "%s must be positive and finite", pointwise ? "scale" : "softmax_scale");
+    if (pointwise && (!(norm > 0.f) || !std::isfinite(norm)))
+        return fail(MTFM_HTA_ERR_INVALID_ARG, "norm must be positive and finite");
     if (batch == 0 || total_kv == 0) return MTFM_HTA_OK;
-    if (!dout || !q || !k || !v || !out || !lse || !dq || !dk || !dv || !q_offsets || !kv_offsets || !hist_len || !n_targets)
+    if (!dout || !q || !k || !v || (!pointwise && (!out || !lse)) || !dq || !dk || !dv || !q_offsets || !kv_offsets ||
+        !hist_len || !n_targets)
         return fail(MTFM_HTA_ERR_INVALID_ARG, "null pointer argument");
     if (misaligned(dout) || misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out) || misaligned(dq) ||
         misaligned(dk) || misaligned(dv))
@@ -291,6 +300,7 @@ static int bwd_impl(const void* dout, const void* q, const void* k, const void* 
     p.batch = batch; p.total_q = total_q; p.total_kv = total_kv; p.max_hist = max_hist; p.max_targets = max_targets;
     p.Hq = Hq; p.Hkv = Hkv; p.d = head_dim; p.scale = softmax_scale; p.layer = layer;
     p.rt_len = rt_len; p.ts = timestamps; p.max_rt = max_rt;
+    p.pointwise = pointwise ? 1 : 0; p.norm = norm;
     if (dtype == MTFM_HTA_BF16) {
         char* base = (char*)workspace;
         p.neg_delta = (float*)(base + w.delta_off);
@@ -333,6 +343,33 @@ int mtfm_hta_bwd_rt(const void* dout, const void* q, const void* k, const void* 
     return bwd_impl(dout, q, k, v, out, lse, dq, dk, dv, q_offsets, kv_offsets, hist_len, rt_len, n_targets, timestamps,
                     batch, total_q, total_kv, max_hist, max_rt, max_targets, Hq, Hkv, head_dim, softmax_scale, dtype, layer,
                     workspace, workspace_bytes, stream);
+}
+
+size_t mtfm_hta_pw_workspace_bytes(int layer, int dtype, int is_bwd, int32_t batch, int64_t total_q, int64_t total_kv,
+                                   int32_t max_hist, int32_t max_targets, int32_t Hq, int32_t Hkv, int32_t head_dim) {
+    if (check_scalars(layer, dtype, batch, total_q, total_kv, max_hist, 0, max_targets, Hq, Hkv, head_dim) != MTFM_HTA_OK)
+        return (size_t)-1;
+    return plan_workspace(dtype, is_bwd, batch, total_q, Hq, false).total;
+}
+
+int mtfm_hta_pw_fwd(const void* q, const void* k, const void* v, void* out, const int32_t* q_offsets,
+                    const int32_t* kv_offsets, const int32_t* hist_len, const int32_t* n_targets, int32_t batch,
+                    int64_t total_q, int64_t total_kv, int32_t max_hist, int32_t max_targets, int32_t Hq, int32_t Hkv,
+                    int32_t head_dim, float scale, float norm, int dtype, int layer, void* workspace,
+                    size_t workspace_bytes, void* stream) {
+    return fwd_impl(q, k, v, out, nullptr, q_offsets, kv_offsets, hist_len, nullptr, n_targets, nullptr, batch, total_q,
+                    total_kv, max_hist, 0, max_targets, Hq, Hkv, head_dim, scale, dtype, layer, workspace, workspace_bytes,
+                    stream, true, norm);
+}
+
+int mtfm_hta_pw_bwd(const void* dout, const void* q, const void* k, const void* v, void* dq, void* dk, void* dv,
+                    const int32_t* q_offsets, const int32_t* kv_offsets, const int32_t* hist_len, const int32_t* n_targets,
+                    int32_t batch, int64_t total_q, int64_t total_kv, int32_t max_hist, int32_t max_targets, int32_t Hq,
+                    int32_t Hkv, int32_t head_dim, float scale, float norm, int dtype, int layer, void* workspace,
+                    size_t workspace_bytes, void* stream) {
+    return bwd_impl(dout, q, k, v, nullptr, nullptr, dq, dk, dv, q_offsets, kv_offsets, hist_len, nullptr, n_targets,
+                    nullptr, batch, total_q, total_kv, max_hist, 0, max_targets, Hq, Hkv, head_dim, scale, dtype, layer,
+                    workspace, workspace_bytes, stream, true, norm);
 }
 
 }  // extern "C"

@@ -40,7 +40,8 @@ __device__ inline float group_sum(float x, int width) {  // sum over aligned gro
 
 // ---------------------------------------------------------------------------------------- self keys
 // One group of D/8 lanes per (target token, kv head); the group walks the r query heads of the kv head.
-template <int D>
+// PW: pointwise weights, p = norm silu(x), ds = norm dp silu'(x) scale (no lse, no delta, `out` is not read).
+template <int D, bool PW = false>
 __global__ __launch_bounds__(256) void bwd_self_kernel(Params p) {
     constexpr int LPR = D / 8;           // lanes per item, 8 elements (16 bytes) each
     constexpr int IPB = 256 / LPR;       // items per block
@@ -70,7 +71,7 @@ __global__ __launch_bounds__(256) void bwd_self_kernel(Params p) {
         const int h = g * r + hh;
         const int64_t off = (q_row * p.Hq + h) * D + sub * 8;
         const bf16x8 dov = *(const bf16x8*)(dog + off);
-        const bf16x8 ov = *(const bf16x8*)(og + off);
+        const bf16x8 ov = PW ? dov : *(const bf16x8*)(og + off);
         const bf16x8 qv = *(const bf16x8*)(qg + off);
         float dof[8], qf[8], part = 0.f, sp = 0.f, dpp = 0.f;
 #pragma unroll
@@ -81,12 +82,19 @@ __global__ __launch_bounds__(256) void bwd_self_kernel(Params p) {
             sp = fmaf(qf[j], kself[j], sp);
             dpp = fmaf(dof[j], vself[j], dpp);
         }
-        const float delta = group_sum(part, LPR);
-        const float lse = p.lse[(int64_t)h * p.total_q + q_row];
         const float sc = group_sum(sp, LPR) * p.scale;
         const float dp = group_sum(dpp, LPR);
-        const float pw = __expf(sc - lse);
-        const float ds = pw * (dp - delta) * p.scale;
+        float pw, ds;
+        if constexpr (PW) {
+            const float sg = 1.f / (1.f + __expf(-sc));
+            pw = p.norm * pw_silu(sc, sg);
+            ds = p.norm * dp * pw_silu_prime(sc, sg) * p.scale;
+        } else {
+            const float delta = group_sum(part, LPR);
+            const float lse = p.lse[(int64_t)h * p.total_q + q_row];
+            pw = __expf(sc - lse);
+            ds = pw * (dp - delta) * p.scale;
+        }
 #pragma unroll
         for (int j = 0; j < 8; j++) {
             dk_t[j] = fmaf(ds, qf[j], dk_t[j]);
@@ -108,8 +116,11 @@ constexpr int BN = 64;  // keys per LDS tile of the dQ kernel
 
 // RT: users with real-time tokens (mask rule 2), handled as in the forward kernel: their keys run through the same
 // tile loop, masked per query row with the row's limit; a real-time row gets its own key in the epilogue.
-template <int D, int RB, int NW, bool RT>
+// PW: the pointwise reading of phi2 -- dS = dP o silu'(scale S), scaled by norm * scale at the store; no lse, no
+// delta, `out` is not read.  The row statistics the dK/dV pass starts its accumulators from are left as zeros.
+template <int D, int RB, int NW, bool RT, bool PW = false>
 __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(Params p, int hpb, int n_hc, int tpg) {
+    static_assert(!(PW && RT), "the pointwise variant is built for samples of history + target tokens");
     using ST = KvStage<D, NW>;
     constexpr int NKS = D / 16, NDB = D / 32, NKB = BN / 32;
     static_assert(ST::BN == BN, "tile height");
@@ -141,6 +152,7 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(Params p, int hpb, i
     const __bf16* kg = (const __bf16*)p.k;
     const __bf16* vg = (const __bf16*)p.v;
     const float c2 = p.scale * LOG2E;
+    const float neg_c2 = -c2;
 
     const int n_kt = (LK + BN - 1) / BN;
     int nat[NKS], tlo[NDB], thi[NDB];  // per-lane element offsets of the operand fragments inside a swizzled tile
@@ -170,10 +182,10 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(Params p, int hpb, i
         for (int ks = 0; ks < NKS; ks++) {
             qf[rb][ks] = *(const bf16x8*)((const __bf16*)p.q + off + ks * 16);
             dof[rb][ks] = *(const bf16x8*)((const __bf16*)p.dout + off + ks * 16);
-            part = dot_bf16x8(part, dof[rb][ks], *(const bf16x8*)((const __bf16*)p.out + off + ks * 16));
+            if constexpr (!PW) part = dot_bf16x8(part, dof[rb][ks], *(const bf16x8*)((const __bf16*)p.out + off + ks * 16));
         }
         const int64_t stat = (int64_t)h * p.total_q + q_base + row;
-        const float lse = p.lse[stat];
+        const float lse = PW ? 0.f : p.lse[stat];
         const float delta = part + other_half(part);
         lse2[rb] = lse * LOG2E;
         dl[rb] = -delta;
@@ -231,7 +243,7 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(Params p, int hpb, i
             for (int v = 0; v < 16; v++) {
                 if (8 * (v / 4) + 4 * hf + (v % 4) >= n_live) {
 #pragma unroll
-                    for (int rb = 0; rb < RB; rb++) S[rb][v] = -INFINITY;
+                    for (int rb = 0; rb < RB; rb++) S[rb][v] = PW ? PW_MASKED : -INFINITY;
                 }
             }
         }
@@ -240,8 +252,13 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(Params p, int hpb, i
         for (int rb = 0; rb < RB; rb++)
 #pragma unroll
             for (int v = 0; v < 16; v++) {
-                const float pw = fast_exp2(fmaf(S[rb][v], c2, -lse2[rb]));
-                dsb[rb][v / 8][v % 8] = (__bf16)(pw * (dP[rb][v] + dl[rb]));
+                if constexpr (PW) {
+                    const float sg = pw_sigmoid(S[rb][v], neg_c2);
+                    dsb[rb][v / 8][v % 8] = (__bf16)(dP[rb][v] * pw_silu_prime(S[rb][v] * p.scale, sg));
+                } else {
+                    const float pw = fast_exp2(fmaf(S[rb][v], c2, -lse2[rb]));
+                    dsb[rb][v / 8][v % 8] = (__bf16)(pw * (dP[rb][v] + dl[rb]));
+                }
             }
         // dQ^T[d][row] += sum_key K[key][d] dS^T[key][row]
 #pragma unroll
@@ -307,8 +324,13 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(Params p, int hpb, i
             }
             sp += other_half(sp);
             dpp += other_half(dpp);
-            const float pw = fast_exp2(fmaf(sp, c2, -lse2[rb]));
-            const float ds = pw * (dpp + dl[rb]);
+            float ds;
+            if constexpr (PW) {
+                ds = dpp * pw_silu_prime(sp * p.scale, pw_sigmoid(sp, neg_c2));
+            } else {
+                const float pw = fast_exp2(fmaf(sp, c2, -lse2[rb]));
+                ds = pw * (dpp + dl[rb]);
+            }
 #pragma unroll
             for (int db = 0; db < NDB; db++)
 #pragma unroll
@@ -326,7 +348,7 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(Params p, int hpb, i
                 for (int v4 = 0; v4 < 4; v4++) {
                     bf16x4 o4;
 #pragma unroll
-                    for (int j = 0; j < 4; j++) o4[j] = (__bf16)(dQ[rb][db][4 * v4 + j] * p.scale);
+                    for (int j = 0; j < 4; j++) o4[j] = (__bf16)(dQ[rb][db][4 * v4 + j] * (PW ? p.scale * p.norm : p.scale));
                     *(bf16x4*)(op + db * 32 + 8 * v4 + 4 * hf) = o4;
                 }
         }
@@ -351,8 +373,11 @@ struct DkdvSmem {
 // other key; a wave whose 32 keys reach past the history takes the masked instruction stream, where a weight
 // survives only if the key lies below the row's limit (p.lim, staged with the row statistics) or is the row's own
 // token (the own key of a real-time row; target rows' own keys are the business of bwd_self_kernel).
-template <int D, int NW, bool RT>
+// PW: the pointwise reading of phi2 -- P = silu(scale S), dS = dP o silu'(scale S); the staged row statistics are
+// zeros for rows that exist (the sentinel for rows that do not still removes them), norm is applied at the store.
+template <int D, int NW, bool RT, bool PW = false>
 __global__ __launch_bounds__(NW * 64, D > 64 ? 1 : 2) void bwd_dkdv_kernel(Params p, int tpg, unsigned per_xcd) {
+    static_assert(!(PW && RT), "the pointwise variant is built for samples of history + target tokens");
     using SM = DkdvSmem<D, NW, RT>;
     static_assert(!RT || NW >= 2 * SM::UPI, "waves UPI .. 2 UPI - 1 copy the rows' limits");
     constexpr int UPI = SM::UPI, NSTAGE = SM::NSTAGE;
@@ -590,6 +615,21 @@ __global__ __launch_bounds__(NW * 64, D > 64 ? 1 : 2) void bwd_dkdv_kernel(Param
             }
             self_row = kw + l32 - tok_shift - (u / r) * 32;
         }
+        if constexpr (PW) {
+#pragma unroll
+            for (int v = 0; v < 16; v++) {
+                const float sg = pw_sigmoid(o.S[v], -c2);
+                const float x = o.S[v] * p.scale;
+                float pw = pw_silu(x, sg), sp = pw_silu_prime(x, sg);
+                if constexpr (MASKED) {  // keys past the history carry no weight
+                    pw = key_live ? pw : 0.f;
+                    sp = key_live ? sp : 0.f;
+                }
+                wt.pb[v / 8][v % 8] = (__bf16)pw;
+                wt.dsb[v / 8][v % 8] = (__bf16)(sp * o.dP[v]);
+            }
+            return;
+        }
 #pragma unroll
         for (int v = 0; v < 16; v++) {
             float pw = fast_exp2(o.S[v] * c2);
@@ -693,8 +733,8 @@ __global__ __launch_bounds__(NW * 64, D > 64 ? 1 : 2) void bwd_dkdv_kernel(Param
                 const int64_t off = ((kv_base + key) * p.Hkv + g) * D + l32;
 #pragma unroll
                 for (int db = 0; db < NDB; db++) {
-                    dkg[off + db * 32] = (__bf16)(dK[db][v] * p.scale);
-                    dvg[off + db * 32] = (__bf16)dV[db][v];
+                    dkg[off + db * 32] = (__bf16)(dK[db][v] * (PW ? p.scale * p.norm : p.scale));
+                    dvg[off + db * 32] = (__bf16)(PW ? dV[db][v] * p.norm : dV[db][v]);
                 }
             }
         }
@@ -729,28 +769,31 @@ hipError_t launch_dq(const Params& p, hipStream_t s) {
     const int64_t n_rt = (rows + BM - 1) / BM;
     const int64_t n_blocks = work_grid((int64_t)p.batch * p.Hkv * n_hc, n_rt);
     if (n_blocks >= (1ll << 31)) return hipErrorInvalidValue;
-    auto kernel = p.rt_len ? bwd_dq_kernel<D, RB, NW, true> : bwd_dq_kernel<D, RB, NW, false>;
+    if (p.pointwise && p.rt_len) return hipErrorInvalidValue;
+    auto kernel = p.pointwise ? bwd_dq_kernel<D, RB, NW, false, true>
+                  : p.rt_len  ? bwd_dq_kernel<D, RB, NW, true> : bwd_dq_kernel<D, RB, NW, false>;
     hipLaunchKernelGGL(kernel, dim3((unsigned)n_blocks), dim3(NW * 64), 0, s, p, hpb, n_hc, (int)n_rt);
     return hipGetLastError();
 }
 
-template <int D, int NW, bool RT>
+template <int D, int NW, bool RT, bool PW = false>
 hipError_t launch_dkdv_as(const Params& p, hipStream_t s) {
     const int64_t keys = max_lead_keys(p);
     if (keys <= 0) return hipSuccess;
     const int64_t n_kt = (keys + NW * 32 - 1) / (NW * 32);
     const int64_t n_items = work_grid((int64_t)p.batch * p.Hkv, n_kt);
     if (n_items >= (1ll << 31)) return hipErrorInvalidValue;
-    const int64_t resident = resident_workgroups<bwd_dkdv_kernel<D, NW, RT>>(NW * 64);
+    const int64_t resident = resident_workgroups<bwd_dkdv_kernel<D, NW, RT, PW>>(NW * 64);
     Params pk = p;
     pk.queue = p.queue + QUEUE_DKDV * N_XCD;
-    hipLaunchKernelGGL((bwd_dkdv_kernel<D, NW, RT>), dim3((unsigned)(n_items < resident ? n_items : resident)), dim3(NW * 64),
+    hipLaunchKernelGGL((bwd_dkdv_kernel<D, NW, RT, PW>), dim3((unsigned)(n_items < resident ? n_items : resident)), dim3(NW * 64),
                        0, s, pk, (int)n_kt, (unsigned)(n_items / N_XCD));
     return hipGetLastError();
 }
 
 template <int D, int NW>
 hipError_t launch_dkdv(const Params& p, hipStream_t s) {
+    if (p.pointwise) return p.rt_len ? hipErrorInvalidValue : launch_dkdv_as<D, NW, false, true>(p, s);
     return p.rt_len ? launch_dkdv_as<D, NW, true>(p, s) : launch_dkdv_as<D, NW, false>(p, s);
 }
 
@@ -760,7 +803,10 @@ hipError_t launch_self(const Params& p, hipStream_t s) {
     constexpr int IPB = 256 / (D / 8);
     const int64_t items = (int64_t)p.max_targets * p.Hkv;
     dim3 grid((unsigned)((items + IPB - 1) / IPB), 1, (unsigned)p.batch);
-    hipLaunchKernelGGL(bwd_self_kernel<D>, grid, dim3(256), 0, s, p);
+    if (p.pointwise)
+        hipLaunchKernelGGL((bwd_self_kernel<D, true>), grid, dim3(256), 0, s, p);
+    else
+        hipLaunchKernelGGL((bwd_self_kernel<D, false>), grid, dim3(256), 0, s, p);
     return hipGetLastError();
 }
 

@@ -39,6 +39,9 @@ struct Params {
     const int32_t* rt_len;  // [B] real-time tokens of each user, between its history and its target tokens
     const int32_t* ts;      // [total_kv] one timestamp per K/V row
     int32_t max_rt;
+    // the pointwise reading of phi2: weights norm * silu(scale s) instead of a row softmax (no lse, no delta)
+    int32_t pointwise;
+    float norm;
     // forward pass split over the keys (few requests: inference); n_splits <= 1 = not split
     int32_t n_splits;
     float* o_part;          // [n_splits][total_q][Hq][d] partial outputs, each normalised by its own sum

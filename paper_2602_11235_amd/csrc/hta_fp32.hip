@@ -61,6 +61,34 @@ __global__ __launch_bounds__(WAVE) void fwd_fp32_kernel(Params p) {
 #pragma unroll
     for (int c = 0; c < DMAX; c++) qr[c] = c < d ? q[c] : 0.f;
 
+    if (p.pointwise) {  // out = norm * sum over the visible keys of silu(scale <q, k>) v
+        float acc[DMAX];
+#pragma unroll
+        for (int c = 0; c < DMAX; c++) acc[c] = 0.f;
+        for (int idx = lane; idx < ri.n_vis; idx += WAVE) {
+            const int key = idx < ri.L ? idx : ri.tok;
+            const float* kj = kb + key * kv_stride;
+            const float* vj = vb + key * kv_stride;
+            float dot = 0.f;
+#pragma unroll
+            for (int c = 0; c < DMAX; c++)
+                if (c < d) dot = fmaf(qr[c], kj[c], dot);
+            const float x = p.scale * dot;
+            const float w = p.norm * x / (1.f + expf(-x));
+#pragma unroll
+            for (int c = 0; c < DMAX; c++)
+                if (c < d) acc[c] = fmaf(w, vj[c], acc[c]);
+        }
+        float* o = (float*)p.out + (ri.q_row * p.Hq + h) * d;
+#pragma unroll
+        for (int c = 0; c < DMAX; c++) {
+            if (c < d) {
+                const float s = wave_sum(acc[c]);
+                if (lane == 0) o[c] = s;
+            }
+        }
+        return;
+    }
     // pass 1: row maximum of the scaled logits
     float m = -INFINITY;
     for (int idx = lane; idx < ri.n_vis; idx += WAVE) {
@@ -114,7 +142,7 @@ __global__ __launch_bounds__(WAVE) void bwd_fp32_kernel(Params p) {
     const int64_t qo = (ri.q_row * p.Hq + h) * d;
     const float* q = (const float*)p.q + qo;
     const float* dout = (const float*)p.dout + qo;
-    const float* out = (const float*)p.out + qo;
+    const float* out = p.pointwise ? nullptr : (const float*)p.out + qo;
     const int64_t kv_stride = (int64_t)p.Hkv * d;
     const int64_t kvo = (ri.kv_base * p.Hkv + g) * d;
     const float* kb = (const float*)p.k + kvo;
@@ -128,9 +156,9 @@ __global__ __launch_bounds__(WAVE) void bwd_fp32_kernel(Params p) {
         qr[c] = c < d ? q[c] : 0.f;
         dor[c] = c < d ? dout[c] : 0.f;
         dqa[c] = 0.f;
-        if (c < d) delta = fmaf(dor[c], out[c], delta);
+        if (c < d && out) delta = fmaf(dor[c], out[c], delta);
     }
-    const float lse = p.lse[(int64_t)h * p.total_q + ri.q_row];
+    const float lse = p.pointwise ? 0.f : p.lse[(int64_t)h * p.total_q + ri.q_row];
     for (int idx = lane; idx < ri.n_vis; idx += WAVE) {
         const int key = idx < ri.L ? idx : ri.tok;
         const float* kj = kb + key * kv_stride;
@@ -143,8 +171,16 @@ __global__ __launch_bounds__(WAVE) void bwd_fp32_kernel(Params p) {
                 dp = fmaf(dor[c], vj[c], dp);
             }
         }
-        const float w = expf(p.scale * dot - lse);
-        const float ds = w * (dp - delta);
+        float w, ds;
+        if (p.pointwise) {  // w = norm silu(x), ds = norm dp silu'(x)
+            const float x = p.scale * dot;
+            const float sg = 1.f / (1.f + expf(-x));
+            w = p.norm * x * sg;
+            ds = p.norm * dp * sg * (1.f + x * (1.f - sg));
+        } else {
+            w = expf(p.scale * dot - lse);
+            ds = w * (dp - delta);
+        }
         const float sds = p.scale * ds;
 #pragma unroll
         for (int c = 0; c < DMAX; c++) {

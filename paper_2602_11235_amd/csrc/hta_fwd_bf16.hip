@@ -35,8 +35,12 @@ constexpr float RESCALE_SLACK = 8.f;  // log2 units a row's logits may exceed it
 // inference).  The grid gets a second dimension: workgroup (x, y) runs key tiles [y, y+1) * n_kt / n_splits of item x
 // and leaves a partial result -- its rows normalised by its own sum, in float32, with the logsumexp of its keys -- in
 // the workspace; split 0 also takes the rows' own keys.  merge_splits_kernel combines the partial results.
-template <int D, int RB, int NW, bool RT, bool SPLIT>
+//
+// PW: the pointwise reading of phi2 -- weights norm * silu(scale s) on the same tiles and mask: no running maximum, no
+// row sum, no lse; the accumulator is scaled by norm at the store.  (Samples of history + target tokens, unsplit.)
+template <int D, int RB, int NW, bool RT, bool SPLIT, bool PW = false>
 __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb, int n_hc, int tpg) {
+    static_assert(!(PW && (RT || SPLIT)), "the pointwise variant is built for plain, unsplit launches");
     using ST = KvStage<D, NW>;
     constexpr int NKS = D / 16, NDB = D / 32, NKB = BN / 32;
     static_assert(ST::BN == BN, "tile height");
@@ -67,6 +71,7 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb,
     const __bf16* kg = (const __bf16*)p.k;
     const __bf16* vg = (const __bf16*)p.v;
     const float c2 = p.scale * LOG2E;  // logits are handled in the log2 domain
+    const float neg_c2 = -c2;
 
     // Q fragments (B operand of S^T = K Q^T): lane = query row, 8 consecutive d values per k-step.
     // Rows past the end of the user are clamped to the last row; their results are never stored.
@@ -142,16 +147,23 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb,
             for (int v = 0; v < 16; v++) {
                 if (8 * (v / 4) + 4 * hf + (v % 4) >= n_live) {
 #pragma unroll
-                    for (int rb = 0; rb < RB; rb++) S[rb][v] = -INFINITY;
+                    for (int rb = 0; rb < RB; rb++) S[rb][v] = PW ? PW_MASKED : -INFINITY;
                 }
             }
         }
+        bf16x8 pf[RB][2];
+        if constexpr (PW) {
+#pragma unroll
+            for (int rb = 0; rb < RB; rb++)
+#pragma unroll
+                for (int v = 0; v < 16; v++)
+                    pf[rb][v / 8][v % 8] = (__bf16)pw_silu(S[rb][v] * p.scale, pw_sigmoid(S[rb][v], neg_c2));
+        } else {
         // Online softmax, one query row per lane (two lanes, 32 apart, share a row).  The reference m[rb]
         // of a row only has to bound its logits from above up to a factor 2^RESCALE_SLACK: weights are
         // exp2(s - m) <= 2^RESCALE_SLACK, sums and outputs share the reference, and the final division by l
         // removes it.  So the accumulators are rescaled only when some row of the wave outgrows the slack,
         // which after the first tiles almost never happens.
-        bf16x8 pf[RB][2];
 #pragma unroll
         for (int rb = 0; rb < RB; rb++) {
             float mx = S[rb][0];
@@ -179,6 +191,7 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb,
             add_bf16x8(l0, l1, pf[rb][0]);
             add_bf16x8(l0, l1, pf[rb][1]);
             l[rb] = l0 + l1;
+        }
         }
         // O^T[d][row] += sum_key V[key][d] P^T[key][row]
 #pragma unroll
@@ -243,12 +256,17 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb,
                 for (int j = 0; j < 8; j++) dot = fmaf((float)qf[rb][ks][j], (float)kk[j], dot);
             }
             dot += other_half(dot);
-            const float s2 = dot * c2;
-            const float m_new = fmaxf(m[rb], s2);
-            const float alpha = fast_exp2(m[rb] - m_new);
-            const float ps = fast_exp2(s2 - m_new);
-            m[rb] = m_new;
-            l[rb] = l[rb] * alpha + (hf == 0 ? ps : 0.f);
+            float alpha = 1.f, ps;
+            if constexpr (PW) {
+                ps = pw_silu(dot * p.scale, pw_sigmoid(dot, neg_c2));
+            } else {
+                const float s2 = dot * c2;
+                const float m_new = fmaxf(m[rb], s2);
+                alpha = fast_exp2(m[rb] - m_new);
+                ps = fast_exp2(s2 - m_new);
+                m[rb] = m_new;
+                l[rb] = l[rb] * alpha + (hf == 0 ? ps : 0.f);
+            }
 #pragma unroll
             for (int db = 0; db < NDB; db++)
 #pragma unroll
@@ -276,7 +294,7 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb,
                 p.lse_part[((int64_t)split * p.Hq + h) * p.total_q + q_base + row] =
                     lt > 0.f ? (m[rb] + __builtin_amdgcn_logf(lt)) * LN2 : -INFINITY;
         } else if (live) {
-            const float inv = 1.f / lt;
+            const float inv = PW ? p.norm : 1.f / lt;
             __bf16* op = og + ((q_base + row) * p.Hq + h) * D;
 #pragma unroll
             for (int db = 0; db < NDB; db++)
@@ -287,7 +305,7 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb,
                     for (int j = 0; j < 4; j++) o4[j] = (__bf16)(O[rb][db][4 * v4 + j] * inv);
                     *(bf16x4*)(op + db * 32 + 8 * v4 + 4 * hf) = o4;
                 }
-            if (hf == 0) p.lse[(int64_t)h * p.total_q + q_base + row] = (m[rb] + __builtin_amdgcn_logf(lt)) * LN2;
+            if (!PW && hf == 0) p.lse[(int64_t)h * p.total_q + q_base + row] = (m[rb] + __builtin_amdgcn_logf(lt)) * LN2;
         }
     }
 }
@@ -347,8 +365,10 @@ Geometry geometry_of(int RB, int NW, int32_t batch, int32_t Hq, int32_t Hkv, int
 template <int D, int RB, int NW>
 hipError_t launch(const Params& p, hipStream_t s) {
     const bool split = p.n_splits > 1;
-    auto kernel = p.rt_len ? (split ? fwd_bf16_kernel<D, RB, NW, true, true> : fwd_bf16_kernel<D, RB, NW, true, false>)
-                           : (split ? fwd_bf16_kernel<D, RB, NW, false, true> : fwd_bf16_kernel<D, RB, NW, false, false>);
+    if (p.pointwise && (split || p.rt_len)) return hipErrorInvalidValue;
+    auto kernel = p.pointwise ? fwd_bf16_kernel<D, RB, NW, false, false, true>
+                  : p.rt_len  ? (split ? fwd_bf16_kernel<D, RB, NW, true, true> : fwd_bf16_kernel<D, RB, NW, true, false>)
+                              : (split ? fwd_bf16_kernel<D, RB, NW, false, true> : fwd_bf16_kernel<D, RB, NW, false, false>);
     const int64_t rows = max_query_rows(p);
     if (rows <= 0) return hipSuccess;
     const Geometry g = geometry_of(RB, NW, p.batch, p.Hq, p.Hkv, rows);

@@ -46,6 +46,15 @@ __device__ inline floatx16 mfma32(bf16x8 a, bf16x8 b, floatx16 c) {
 
 __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Pointwise weights (the SiLU reading of phi2) for a raw dot product s, x = scale s:
+//   sigma = 1 / (1 + 2^(-x log2 e)),  silu(x) = x sigma,  silu'(x) = sigma (1 + x (1 - sigma)).
+// neg_c2 = -scale log2(e).  A masked entry carries s = -1e30 (finite on purpose): then sigma is exactly 0 and both
+// results are zero, where -inf would give inf * 0.
+constexpr float PW_MASKED = -1e30f;
+__device__ inline float pw_sigmoid(float s, float neg_c2) { return __builtin_amdgcn_rcpf(1.f + fast_exp2(s * neg_c2)); }
+__device__ inline float pw_silu(float x, float sg) { return x * sg; }
+__device__ inline float pw_silu_prime(float x, float sg) { return fmaf(sg, x * (1.f - sg), sg); }
+
 // value held by the lane 32 positions away (the other half of the wave); v_permlane32_swap is a VALU
 // exchange of the upper half of its first operand with the lower half of its second
 __device__ inline float other_half(float x) {

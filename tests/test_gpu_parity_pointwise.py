@@ -1,0 +1,123 @@
+"""GPU parity of the pointwise variant (weights norm * silu(scale s) instead of a row softmax) against the float64
+oracle, element by element through the C ABI.  Tolerances as for the softmax reading: atol = rtol = 2e-2 (bf16, where
+the weights and dS are rounded to bf16 before their matrix products), 1e-4 (fp32)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import hta_oracle as O
+from paper_2602_11235_amd import hta_pw, inputs
+from tests.hta_testlib import assert_close, host, pick_users, say, to_torch
+
+pytestmark = pytest.mark.gpu
+FULL, TARGET = inputs.LAYER_FULL, inputs.LAYER_TARGET
+
+
+def norm_of(case):
+    """HSTU divides the weights by the sequence length: the reciprocal of the longest sample of the batch."""
+    n = int((case.hist_len + case.n_targets).max()) if case.batch else 1
+    return 1.0 / max(n, 1)
+
+
+def device_batch(case, norm):
+    dt = case.cfg.dtype
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to("cuda")
+    return hta_pw.PointwiseBatch(to_torch(case.q, dt), to_torch(case.k, dt), to_torch(case.v, dt), dev(case.q_offsets),
+                                 dev(case.kv_offsets), dev(case.hist_len), dev(case.n_targets),
+                                 int(case.hist_len.max()) if case.batch else 0,
+                                 int(case.n_targets.max()) if case.batch else 0, case.scale, norm, case.cfg.layer)
+
+
+def close_on_tensor_scale(name, got, ref, dtype):
+    """For weights that are not normalised: an element is a sum of terms far larger than itself can be, and the bf16
+    rounding of each term (2^-9 relative) is what the error is made of, so the bound is relative to the tensor."""
+    rtol = 2e-2 if dtype == "bf16" else 1e-4
+    assert np.isfinite(got).all(), f"{name}: non-finite values in GPU result"
+    err = np.abs(got - ref).max()
+    say(f"    {name}: max abs err {err:.3e}  ref absmax {np.abs(ref).max():.3e}")
+    assert err <= rtol * np.abs(ref).max(), f"{name}: max abs err {err:.3e} exceeds {rtol:g} x max|ref|"
+
+
+def check(case, users=None, norm=None, kv_group=None, compare=assert_close):
+    dt = case.cfg.dtype
+    norm = norm_of(case) if norm is None else norm
+    say(f"  pointwise {case.cfg.name}: layer={case.cfg.layer} B={case.batch} total_q={case.total_q} Hq={case.cfg.Hq} "
+        f"Hkv={case.cfg.Hkv} d={case.cfg.head_dim} {dt} norm={norm:.3e}")
+    b = device_batch(case, norm)
+    out = b.forward()
+    dq, dk, dv = b.backward(to_torch(case.dout, dt))
+    torch.cuda.synchronize()
+    g = dict(out=host(out), dq=host(dq), dk=host(dk), dv=host(dv))
+    ref_case, qrows, kvrows = case, slice(None), slice(None)
+    if users is not None:
+        ref_case = inputs.take_users(case, users)
+        qrows, kvrows = inputs.user_rows(case.q_offsets, users), inputs.user_rows(case.kv_offsets, users)
+    hs, gs = slice(None), slice(None)
+    if kv_group is not None:   # one kv head and its query heads (heads of different kv heads are independent)
+        r = case.cfg.Hq // case.cfg.Hkv
+        hs, gs = slice(kv_group * r, (kv_group + 1) * r), slice(kv_group, kv_group + 1)
+        ref_case = inputs.take_kv_group(ref_case, kv_group)
+    c = ref_case
+    r_out = O.forward_pointwise(c.q, c.k, c.v, c.q_offsets, c.kv_offsets, c.hist_len, c.n_targets, c.scale, norm,
+                                c.cfg.layer)
+    r_dq, r_dk, r_dv = O.backward_pointwise(c.dout, c.q, c.k, c.v, c.q_offsets, c.kv_offsets, c.hist_len, c.n_targets,
+                                            c.scale, norm, c.cfg.layer)
+    compare("out", g["out"][qrows][:, hs], r_out, dt)
+    compare("dq", g["dq"][qrows][:, hs], r_dq, dt)
+    compare("dk", g["dk"][kvrows][:, gs], r_dk, dt)
+    compare("dv", g["dv"][kvrows][:, gs], r_dv, dt)
+
+
+# histories around the 32 / 64 / 128-key boundaries, users without history, without targets, with nothing
+EDGE_HIST = [0, 1, 63, 64, 65, 130, 200, 0, 257, 96, 0, 40]
+EDGE_TGTS = [3, 0, 70, 1, 33, 2, 64, 0, 129, 0, 1, 7]
+
+
+@pytest.mark.parametrize("layer", [FULL, TARGET])
+def test_fp32_edge_cases(layer):
+    check(inputs.make_case(inputs.custom_config("pw_fp32", layer, EDGE_HIST, EDGE_TGTS, 6, 2, 24, dtype="fp32", std=0.5,
+                                                seed=51)))
+
+
+@pytest.mark.parametrize("layer", [FULL, TARGET])
+@pytest.mark.parametrize("Hq,Hkv,d", [(8, 2, 64), (4, 4, 64), (3, 1, 64), (16, 2, 128), (16, 1, 64), (4, 2, 32), (6, 1, 128)])
+def test_bf16_edge_cases(layer, Hq, Hkv, d):
+    check(inputs.make_case(inputs.custom_config(f"pw_{Hq}_{Hkv}_{d}", layer, EDGE_HIST, EDGE_TGTS, Hq, Hkv, d, seed=52)))
+
+
+def test_c1_and_c2_whole():
+    check(inputs.make_case(inputs.CONFIGS["C1"]))
+    check(inputs.make_case(inputs.CONFIGS["C2"]))
+
+
+def test_c3_sampled_users():
+    c = inputs.make_case(inputs.CONFIGS["C3"])
+    check(c, users=pick_users(c, 2))
+
+
+def test_c4_target_layer_sampled_users():
+    c = inputs.make_case(inputs.CONFIGS["C4"])
+    check(c, users=[0, 255, 511])
+
+
+def test_c5_long_histories_sampled_users():
+    c = inputs.make_case(inputs.CONFIGS["C5"])
+    L = c.hist_len
+    order = np.argsort(L)
+    # the shortest, a median and a longer (not the capped 8192: the oracle runs one thread per kv head) history, one kv group
+    users = [int(order[0]), int(order[len(L) // 2]), int(order[int(len(L) * 0.7)])]
+    say(f"  histories {[int(L[u]) for u in users]}")
+    check(c, users=users, kv_group=1)
+
+
+def test_large_logits_and_unit_norm():
+    """Logits far into both tails of the SiLU (weights ~ x and ~ 0) with norm = 1."""
+    c = inputs.make_case(inputs.custom_config("pw_big", FULL, [100, 70], [5, 9], 8, 2, 64, std=1.5, seed=53))
+    check(c, norm=1.0, compare=close_on_tensor_scale)
+
+
+def test_a_small_batch_is_not_split_and_needs_no_saved_state():
+    c = inputs.make_case(inputs.CONFIGS["I1"])
+    b = device_batch(c, norm_of(c))
+    assert b.fwd_ws is not None and b.fwd_ws.numel() == 512   # schedule region only: no partial results
+    check(c)
