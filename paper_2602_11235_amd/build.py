@@ -1,9 +1,12 @@
 """Compile the HIP sources under csrc/ into paper_2602_11235_amd/libmtfm_hta.so for gfx950."""
 from __future__ import annotations
 
+import concurrent.futures
 import glob
 import os
+import shutil
 import subprocess
+import tempfile
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
@@ -21,10 +24,7 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
-def build(verbose: bool = False, extra_flags=()) -> str:
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    tmp = LIB + f".tmp{os.getpid()}"
-    cmd = [hipcc, *HIPCC_FLAGS, *extra_flags, "-o", tmp, *sources()]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd))
     proc = subprocess.run(cmd, capture_output=True, text=True)
@@ -34,7 +34,26 @@ def build(verbose: bool = False, extra_flags=()) -> str:
         raise RuntimeError(f"hipcc failed:\n{err}")
     if verbose and err.strip():
         print(err)
-    os.replace(tmp, LIB)
+
+
+def build(verbose: bool = False, extra_flags=()) -> str:
+    """Compile every source to an object file (in parallel, one hipcc per file), link, and move the library into place
+    only when all of it succeeded."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    compile_flags = [f for f in HIPCC_FLAGS if f != "-shared"]
+    srcs = sources()
+    with tempfile.TemporaryDirectory(prefix="mtfm_hta_build_") as tmp:
+        objs = [os.path.join(tmp, os.path.basename(src) + ".o") for src in srcs]
+        jobs = [[hipcc, *compile_flags, *extra_flags, "-c", "-o", obj, src] for src, obj in zip(srcs, objs)]
+        workers = max(1, min(len(jobs), int(os.environ.get("MAX_JOBS", os.cpu_count() or 1))))
+        with concurrent.futures.ThreadPoolExecutor(workers) as pool:
+            list(pool.map(lambda cmd: _run(cmd, verbose), jobs))
+        out = os.path.join(tmp, "libmtfm_hta.so")
+        _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-fvisibility=hidden", "-o", out, *objs], verbose)
+        staged = LIB + f".tmp{os.getpid()}"
+        shutil.copyfile(out, staged)
+    os.chmod(staged, 0o755)
+    os.replace(staged, LIB)
     return LIB
 
 
