@@ -681,14 +681,30 @@ __global__ __launch_bounds__(NW * 64, D > 64 ? 1 : 2) void bwd_dkdv_kernel(Param
             Operands nxt;
             Transposed f;
             Weights wt;
-            scores(cur);
-            load_transposed(base, f);
-            weights(cur, wt, ragged, base, it * UPI);
-            load_operands(base + SM::UNIT_BYTES, nxt);
-            accumulate(wt, f);
-            scores(nxt);
-            load_transposed(base + SM::UNIT_BYTES, f);
-            weights(nxt, wt, ragged, base + SM::UNIT_BYTES, it * UPI + 1);
+            if constexpr (RT) {
+                scores(cur);
+                load_transposed(base, f);
+                weights(cur, wt, ragged, base, it * UPI);
+                load_operands(base + SM::UNIT_BYTES, nxt);
+                accumulate(wt, f);
+                scores(nxt);
+                load_transposed(base + SM::UNIT_BYTES, f);
+                weights(nxt, wt, ragged, base + SM::UNIT_BYTES, it * UPI + 1);
+            } else {
+                // The second unit's S and dP are requested before the first unit's weights are formed, and the first
+                // unit's accumulations come after the second unit's weights: each block of vector work then has matrix
+                // instructions of the other unit in the stream around it (3 % at d = 64, 6 % at d = 128; the
+                // real-time variant keeps the shorter live ranges, it has no registers to spare).
+                Weights wt0;
+                scores(cur);
+                load_operands(base + SM::UNIT_BYTES, nxt);
+                weights(cur, wt0, ragged, base, it * UPI);
+                scores(nxt);
+                load_transposed(base, f);
+                weights(nxt, wt, ragged, base + SM::UNIT_BYTES, it * UPI + 1);
+                accumulate(wt0, f);
+                load_transposed(base + SM::UNIT_BYTES, f);
+            }
             // copies of iteration it+1 must have landed; those of it+2 may stay in flight
             if (it + 2 < n_iter) wait_all_but_iterations(c1); else wait_all_but_iterations(c0);
             lds_barrier();
