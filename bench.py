@@ -360,11 +360,10 @@ def main() -> int:
     if case.rt_len is not None:  # samples with real-time tokens: the *_rt entry points
         rt = dict(rt_len=dev(case.rt_len), timestamps=dev(case.timestamps), max_rt=int(case.rt_len.max()))
     if pointwise:  # weights norm * silu(scale s); norm = 1 / longest sample, as HSTU divides by the sequence length
-        assert case.rt_len is None, "the pointwise variant takes samples of history + target tokens"
-        pw_norm = 1.0 / float((case.hist_len + case.n_targets).max())
+        longest = case.hist_len + case.n_targets + (0 if case.rt_len is None else case.rt_len)
         batch = hta_pw.PointwiseBatch(dev(case.q), dev(case.k), dev(case.v), dev(case.q_offsets), dev(case.kv_offsets),
                                       dev(case.hist_len), dev(case.n_targets), int(case.hist_len.max()),
-                                      int(case.n_targets.max()), case.scale, pw_norm, cfg.layer)
+                                      int(case.n_targets.max()), case.scale, 1.0 / float(longest.max()), cfg.layer, **rt)
     else:
         batch = hta.Batch(dev(case.q), dev(case.k), dev(case.v), dev(case.q_offsets), dev(case.kv_offsets),
                           dev(case.hist_len), dev(case.n_targets), int(case.hist_len.max()), int(case.n_targets.max()),

@@ -12,8 +12,9 @@
  * pass needs neither the forward output nor anything saved by the forward pass.  Backward, with x_ij = scale <q_i, k_j>:
  *   dv_j = norm sum_i silu(x_ij) dout_i        dx_ij = norm <dout_i, v_j> silu'(x_ij),  silu'(x) = s (1 + x (1 - s)), s = sigmoid(x)
  *   dq_i = scale sum_j dx_ij k_j               dk_j = scale sum_i dx_ij q_i             (sums over the query heads of a kv head)
- * Built for samples of history + target tokens (no real-time segment); bf16 with head_dim in {32, 64, 128} on the
- * MFMA kernels, fp32 on the debug path, as in mtfm_hta.h.
+ * bf16 with head_dim in {32, 64, 128} on the MFMA kernels, fp32 on the debug path, as in mtfm_hta.h.  The functions
+ * with the _rt suffix take samples with real-time tokens (mask rule 2), with the arguments and the readings of the
+ * _rt functions of mtfm_hta.h.  A forward call is never split over the keys here.
  */
 #ifndef MTFM_HTA_PW_H
 #define MTFM_HTA_PW_H
@@ -44,6 +45,23 @@ MTFM_HTA_API int mtfm_hta_pw_bwd(const void* dout, const void* q, const void* k,
                  const int32_t* n_targets, int32_t batch, int64_t total_q, int64_t total_kv, int32_t max_hist,
                  int32_t max_targets, int32_t Hq, int32_t Hkv, int32_t head_dim, float scale, float norm, int dtype,
                  int layer, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Samples with real-time tokens: rt_len [batch] and timestamps [total_kv] (int32, device) and the bound max_rt are
+ * extra, as in mtfm_hta_fwd_rt / mtfm_hta_bwd_rt; the workspace also holds one int32 per query row. */
+MTFM_HTA_API size_t mtfm_hta_pw_workspace_bytes_rt(int layer, int dtype, int is_bwd, int32_t batch, int64_t total_q,
+                                int64_t total_kv, int32_t max_hist, int32_t max_rt, int32_t max_targets, int32_t Hq,
+                                int32_t Hkv, int32_t head_dim);
+MTFM_HTA_API int mtfm_hta_pw_fwd_rt(const void* q, const void* k, const void* v, void* out, const int32_t* q_offsets,
+                 const int32_t* kv_offsets, const int32_t* hist_len, const int32_t* rt_len, const int32_t* n_targets,
+                 const int32_t* timestamps, int32_t batch, int64_t total_q, int64_t total_kv, int32_t max_hist,
+                 int32_t max_rt, int32_t max_targets, int32_t Hq, int32_t Hkv, int32_t head_dim, float scale, float norm,
+                 int dtype, int layer, void* workspace, size_t workspace_bytes, void* stream);
+MTFM_HTA_API int mtfm_hta_pw_bwd_rt(const void* dout, const void* q, const void* k, const void* v, void* dq, void* dk,
+                 void* dv, const int32_t* q_offsets, const int32_t* kv_offsets, const int32_t* hist_len,
+                 const int32_t* rt_len, const int32_t* n_targets, const int32_t* timestamps, int32_t batch,
+                 int64_t total_q, int64_t total_kv, int32_t max_hist, int32_t max_rt, int32_t max_targets, int32_t Hq,
+                 int32_t Hkv, int32_t head_dim, float scale, float norm, int dtype, int layer, void* workspace,
+                 size_t workspace_bytes, void* stream);
 
 #ifdef __cplusplus
 }

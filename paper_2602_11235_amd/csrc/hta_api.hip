@@ -372,4 +372,35 @@ int mtfm_hta_pw_bwd(const void* dout, const void* q, const void* k, const void* 
                     workspace, workspace_bytes, stream, true, norm);
 }
 
+size_t mtfm_hta_pw_workspace_bytes_rt(int layer, int dtype, int is_bwd, int32_t batch, int64_t total_q, int64_t total_kv,
+                                      int32_t max_hist, int32_t max_rt, int32_t max_targets, int32_t Hq, int32_t Hkv,
+                                      int32_t head_dim) {
+    if (check_scalars(layer, dtype, batch, total_q, total_kv, max_hist, max_rt, max_targets, Hq, Hkv, head_dim) != MTFM_HTA_OK)
+        return (size_t)-1;
+    return plan_workspace(dtype, is_bwd, batch, total_q, Hq, true).total;
+}
+
+int mtfm_hta_pw_fwd_rt(const void* q, const void* k, const void* v, void* out, const int32_t* q_offsets,
+                       const int32_t* kv_offsets, const int32_t* hist_len, const int32_t* rt_len, const int32_t* n_targets,
+                       const int32_t* timestamps, int32_t batch, int64_t total_q, int64_t total_kv, int32_t max_hist,
+                       int32_t max_rt, int32_t max_targets, int32_t Hq, int32_t Hkv, int32_t head_dim, float scale,
+                       float norm, int dtype, int layer, void* workspace, size_t workspace_bytes, void* stream) {
+    if (batch > 0 && total_q > 0 && (!rt_len || !timestamps)) return fail(MTFM_HTA_ERR_INVALID_ARG, "null pointer argument");
+    return fwd_impl(q, k, v, out, nullptr, q_offsets, kv_offsets, hist_len, rt_len, n_targets, timestamps, batch, total_q,
+                    total_kv, max_hist, max_rt, max_targets, Hq, Hkv, head_dim, scale, dtype, layer, workspace,
+                    workspace_bytes, stream, true, norm);
+}
+
+int mtfm_hta_pw_bwd_rt(const void* dout, const void* q, const void* k, const void* v, void* dq, void* dk, void* dv,
+                       const int32_t* q_offsets, const int32_t* kv_offsets, const int32_t* hist_len, const int32_t* rt_len,
+                       const int32_t* n_targets, const int32_t* timestamps, int32_t batch, int64_t total_q, int64_t total_kv,
+                       int32_t max_hist, int32_t max_rt, int32_t max_targets, int32_t Hq, int32_t Hkv, int32_t head_dim,
+                       float scale, float norm, int dtype, int layer, void* workspace, size_t workspace_bytes,
+                       void* stream) {
+    if (batch > 0 && total_kv > 0 && (!rt_len || !timestamps)) return fail(MTFM_HTA_ERR_INVALID_ARG, "null pointer argument");
+    return bwd_impl(dout, q, k, v, nullptr, nullptr, dq, dk, dv, q_offsets, kv_offsets, hist_len, rt_len, n_targets,
+                    timestamps, batch, total_q, total_kv, max_hist, max_rt, max_targets, Hq, Hkv, head_dim, scale, dtype,
+                    layer, workspace, workspace_bytes, stream, true, norm);
+}
+
 }  // extern "C"

@@ -120,7 +120,6 @@ constexpr int BN = 64;  // keys per LDS tile of the dQ kernel
 // delta, `out` is not read.  The row statistics the dK/dV pass starts its accumulators from are left as zeros.
 template <int D, int RB, int NW, bool RT, bool PW = false>
 __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(Params p, int hpb, int n_hc, int tpg) {
-    static_assert(!(PW && RT), "the pointwise variant is built for samples of history + target tokens");
     using ST = KvStage<D, NW>;
     constexpr int NKS = D / 16, NDB = D / 32, NKB = BN / 32;
     static_assert(ST::BN == BN, "tile height");
@@ -235,7 +234,7 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(Params p, int hpb, i
                 const int rel = lim[rb] - k0;
                 static_for<0, 16>([&](auto V) {
                     constexpr int v = decltype(V)::value;
-                    S[rb][v] = (8 * (v / 4) + 4 * hf + (v % 4) >= rel) ? -INFINITY : S[rb][v];
+                    S[rb][v] = (8 * (v / 4) + 4 * hf + (v % 4) >= rel) ? (PW ? PW_MASKED : -INFINITY) : S[rb][v];
                 });
             });
         } else if (n_live < 32) {  // ragged: keys >= L_b are not visible (P = 0)
@@ -377,7 +376,6 @@ struct DkdvSmem {
 // zeros for rows that exist (the sentinel for rows that do not still removes them), norm is applied at the store.
 template <int D, int NW, bool RT, bool PW = false>
 __global__ __launch_bounds__(NW * 64, D > 64 ? 1 : 2) void bwd_dkdv_kernel(Params p, int tpg, unsigned per_xcd) {
-    static_assert(!(PW && RT), "the pointwise variant is built for samples of history + target tokens");
     using SM = DkdvSmem<D, NW, RT>;
     static_assert(!RT || NW >= 2 * SM::UPI, "waves UPI .. 2 UPI - 1 copy the rows' limits");
     constexpr int UPI = SM::UPI, NSTAGE = SM::NSTAGE;
@@ -621,7 +619,12 @@ __global__ __launch_bounds__(NW * 64, D > 64 ? 1 : 2) void bwd_dkdv_kernel(Param
                 const float sg = pw_sigmoid(o.S[v], -c2);
                 const float x = o.S[v] * p.scale;
                 float pw = pw_silu(x, sg), sp = pw_silu_prime(x, sg);
-                if constexpr (MASKED) {  // keys past the history carry no weight
+                if constexpr (MASKED && RT) {
+                    const int key = kw + l32;
+                    const bool vis = key < limv[v] || (key_live && self_row == 8 * (v / 4) + 4 * hf + (v % 4));
+                    pw = vis ? pw : 0.f;
+                    sp = vis ? sp : 0.f;
+                } else if constexpr (MASKED) {  // keys past the history carry no weight
                     pw = key_live ? pw : 0.f;
                     sp = key_live ? sp : 0.f;
                 }
@@ -785,8 +788,7 @@ hipError_t launch_dq(const Params& p, hipStream_t s) {
     const int64_t n_rt = (rows + BM - 1) / BM;
     const int64_t n_blocks = work_grid((int64_t)p.batch * p.Hkv * n_hc, n_rt);
     if (n_blocks >= (1ll << 31)) return hipErrorInvalidValue;
-    if (p.pointwise && p.rt_len) return hipErrorInvalidValue;
-    auto kernel = p.pointwise ? bwd_dq_kernel<D, RB, NW, false, true>
+    auto kernel = p.pointwise ? (p.rt_len ? bwd_dq_kernel<D, RB, NW, true, true> : bwd_dq_kernel<D, RB, NW, false, true>)
                   : p.rt_len  ? bwd_dq_kernel<D, RB, NW, true> : bwd_dq_kernel<D, RB, NW, false>;
     hipLaunchKernelGGL(kernel, dim3((unsigned)n_blocks), dim3(NW * 64), 0, s, p, hpb, n_hc, (int)n_rt);
     return hipGetLastError();
@@ -809,7 +811,7 @@ hipError_t launch_dkdv_as(const Params& p, hipStream_t s) {
 
 template <int D, int NW>
 hipError_t launch_dkdv(const Params& p, hipStream_t s) {
-    if (p.pointwise) return p.rt_len ? hipErrorInvalidValue : launch_dkdv_as<D, NW, false, true>(p, s);
+    if (p.pointwise) return p.rt_len ? launch_dkdv_as<D, NW, true, true>(p, s) : launch_dkdv_as<D, NW, false, true>(p, s);
     return p.rt_len ? launch_dkdv_as<D, NW, true>(p, s) : launch_dkdv_as<D, NW, false>(p, s);
 }
 

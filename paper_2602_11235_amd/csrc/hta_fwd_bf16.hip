@@ -37,10 +37,10 @@ constexpr float RESCALE_SLACK = 8.f;  // log2 units a row's logits may exceed it
 // the workspace; split 0 also takes the rows' own keys.  merge_splits_kernel combines the partial results.
 //
 // PW: the pointwise reading of phi2 -- weights norm * silu(scale s) on the same tiles and mask: no running maximum, no
-// row sum, no lse; the accumulator is scaled by norm at the store.  (Samples of history + target tokens, unsplit.)
+// row sum, no lse; the accumulator is scaled by norm at the store.  (Unsplit launches only.)
 template <int D, int RB, int NW, bool RT, bool SPLIT, bool PW = false>
 __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb, int n_hc, int tpg) {
-    static_assert(!(PW && (RT || SPLIT)), "the pointwise variant is built for plain, unsplit launches");
+    static_assert(!(PW && SPLIT), "the pointwise variant is built for unsplit launches");
     using ST = KvStage<D, NW>;
     constexpr int NKS = D / 16, NDB = D / 32, NKB = BN / 32;
     static_assert(ST::BN == BN, "tile height");
@@ -139,7 +139,7 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb,
                 const int rel = lim[rb] - k0;
                 static_for<0, 16>([&](auto V) {
                     constexpr int v = decltype(V)::value;
-                    S[rb][v] = (8 * (v / 4) + 4 * hf + (v % 4) >= rel) ? -INFINITY : S[rb][v];
+                    S[rb][v] = (8 * (v / 4) + 4 * hf + (v % 4) >= rel) ? (PW ? PW_MASKED : -INFINITY) : S[rb][v];
                 });
             });
         } else if (n_live < 32) {  // ragged: keys >= L_b are not visible
@@ -365,8 +365,8 @@ Geometry geometry_of(int RB, int NW, int32_t batch, int32_t Hq, int32_t Hkv, int
 template <int D, int RB, int NW>
 hipError_t launch(const Params& p, hipStream_t s) {
     const bool split = p.n_splits > 1;
-    if (p.pointwise && (split || p.rt_len)) return hipErrorInvalidValue;
-    auto kernel = p.pointwise ? fwd_bf16_kernel<D, RB, NW, false, false, true>
+    if (p.pointwise && split) return hipErrorInvalidValue;
+    auto kernel = p.pointwise ? (p.rt_len ? fwd_bf16_kernel<D, RB, NW, true, false, true> : fwd_bf16_kernel<D, RB, NW, false, false, true>)
                   : p.rt_len  ? (split ? fwd_bf16_kernel<D, RB, NW, true, true> : fwd_bf16_kernel<D, RB, NW, true, false>)
                               : (split ? fwd_bf16_kernel<D, RB, NW, false, true> : fwd_bf16_kernel<D, RB, NW, false, false>);
     const int64_t rows = max_query_rows(p);

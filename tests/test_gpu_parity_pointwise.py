@@ -15,17 +15,22 @@ FULL, TARGET = inputs.LAYER_FULL, inputs.LAYER_TARGET
 
 def norm_of(case):
     """HSTU divides the weights by the sequence length: the reciprocal of the longest sample of the batch."""
-    n = int((case.hist_len + case.n_targets).max()) if case.batch else 1
+    rt = 0 if case.rt_len is None else case.rt_len
+    n = int((case.hist_len + rt + case.n_targets).max()) if case.batch else 1
     return 1.0 / max(n, 1)
 
 
 def device_batch(case, norm):
     dt = case.cfg.dtype
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to("cuda")
+    rt = {}
+    if case.rt_len is not None:
+        rt = dict(rt_len=dev(case.rt_len), timestamps=dev(case.timestamps),
+                  max_rt=int(case.rt_len.max()) if case.batch else 0)
     return hta_pw.PointwiseBatch(to_torch(case.q, dt), to_torch(case.k, dt), to_torch(case.v, dt), dev(case.q_offsets),
                                  dev(case.kv_offsets), dev(case.hist_len), dev(case.n_targets),
                                  int(case.hist_len.max()) if case.batch else 0,
-                                 int(case.n_targets.max()) if case.batch else 0, case.scale, norm, case.cfg.layer)
+                                 int(case.n_targets.max()) if case.batch else 0, case.scale, norm, case.cfg.layer, **rt)
 
 
 def close_on_tensor_scale(name, got, ref, dtype):
@@ -58,10 +63,11 @@ def check(case, users=None, norm=None, kv_group=None, compare=assert_close):
         hs, gs = slice(kv_group * r, (kv_group + 1) * r), slice(kv_group, kv_group + 1)
         ref_case = inputs.take_kv_group(ref_case, kv_group)
     c = ref_case
+    rt = dict(rt_len=c.rt_len, timestamps=c.timestamps)
     r_out = O.forward_pointwise(c.q, c.k, c.v, c.q_offsets, c.kv_offsets, c.hist_len, c.n_targets, c.scale, norm,
-                                c.cfg.layer)
+                                c.cfg.layer, **rt)
     r_dq, r_dk, r_dv = O.backward_pointwise(c.dout, c.q, c.k, c.v, c.q_offsets, c.kv_offsets, c.hist_len, c.n_targets,
-                                            c.scale, norm, c.cfg.layer)
+                                            c.scale, norm, c.cfg.layer, **rt)
     compare("out", g["out"][qrows][:, hs], r_out, dt)
     compare("dq", g["dq"][qrows][:, hs], r_dq, dt)
     compare("dk", g["dk"][kvrows][:, gs], r_dk, dt)
@@ -83,6 +89,31 @@ def test_fp32_edge_cases(layer):
 @pytest.mark.parametrize("Hq,Hkv,d", [(8, 2, 64), (4, 4, 64), (3, 1, 64), (16, 2, 128), (16, 1, 64), (4, 2, 32), (6, 1, 128)])
 def test_bf16_edge_cases(layer, Hq, Hkv, d):
     check(inputs.make_case(inputs.custom_config(f"pw_{Hq}_{Hkv}_{d}", layer, EDGE_HIST, EDGE_TGTS, Hq, Hkv, d, seed=52)))
+
+
+# with real-time tokens (mask rule 2): the segment lengths of the softmax edge tests
+RT_HIST = [0, 1, 63, 64, 65, 130, 200, 0, 257, 96, 0, 40]
+RT_RT = [5, 0, 3, 70, 31, 2, 140, 0, 33, 32, 64, 0]
+RT_TGTS = [3, 0, 70, 1, 33, 2, 64, 0, 129, 0, 1, 7]
+
+
+@pytest.mark.parametrize("layer", [FULL, TARGET])
+def test_fp32_realtime_edge_cases(layer):
+    check(inputs.make_case(inputs.custom_config("pw_rt_fp32", layer, RT_HIST, RT_TGTS, 6, 2, 24, dtype="fp32", std=0.5,
+                                                seed=54, rt_len=RT_RT)))
+
+
+@pytest.mark.parametrize("layer", [FULL, TARGET])
+@pytest.mark.parametrize("Hq,Hkv,d", [(8, 2, 64), (3, 1, 64), (16, 2, 128), (4, 2, 32)])
+def test_bf16_realtime_edge_cases(layer, Hq, Hkv, d):
+    check(inputs.make_case(inputs.custom_config(f"pw_rt_{Hq}_{Hkv}_{d}", layer, RT_HIST, RT_TGTS, Hq, Hkv, d, seed=55,
+                                                rt_len=RT_RT)))
+
+
+def test_c2_rt_whole_and_c3_rt_sampled_users():
+    check(inputs.make_case(inputs.CONFIGS["C2_RT"]))
+    c = inputs.make_case(inputs.CONFIGS["C3_RT"])
+    check(c, users=pick_users(c, 1))
 
 
 def test_c1_and_c2_whole():

@@ -13,7 +13,7 @@ FAKE = 0x1000
 def test_library_exports_every_declared_symbol():
     text = open(os.path.join(ROOT, "include", "mtfm_hta_pw.h")).read()
     names = sorted(set(re.findall(r"MTFM_HTA_API[^;(]*?\b(mtfm_hta_pw_\w+)\s*\(", text)))
-    assert set(names) == set(hta_pw.EXPORTS) and len(names) == 3
+    assert set(names) == set(hta_pw.EXPORTS) and len(names) == 6
     lib = hta_pw.load_library()
     for n in names:
         assert getattr(lib, n) is not None
