@@ -14,7 +14,8 @@
  *   dq_i = scale sum_j dx_ij k_j               dk_j = scale sum_i dx_ij q_i             (sums over the query heads of a kv head)
  * bf16 with head_dim in {32, 64, 128} on the MFMA kernels, fp32 on the debug path, as in mtfm_hta.h.  The functions
  * with the _rt suffix take samples with real-time tokens (mask rule 2), with the arguments and the readings of the
- * _rt functions of mtfm_hta.h.  A forward call is never split over the keys here.
+ * _rt functions of mtfm_hta.h.  A forward call on a few users splits the keys over workgroups as mtfm_hta_fwd does
+ * (the partial results are partial sums here); the workspace functions account for it.
  */
 #ifndef MTFM_HTA_PW_H
 #define MTFM_HTA_PW_H
@@ -26,7 +27,8 @@ extern "C" {
 #endif
 
 /* Bytes of device workspace a call needs (pure host arithmetic; (size_t)-1 for invalid arguments): the schedule
- * region of mtfm_hta.h and, for the bf16 backward pass, two float32 values per (query head, query row). */
+ * region of mtfm_hta.h, the partial results of a forward call that splits its keys, and, for the bf16 backward
+ * pass, two float32 values per (query head, query row). */
 MTFM_HTA_API size_t mtfm_hta_pw_workspace_bytes(int layer, int dtype, int is_bwd, int32_t batch, int64_t total_q,
                                 int64_t total_kv, int32_t max_hist, int32_t max_targets, int32_t Hq, int32_t Hkv,
                                 int32_t head_dim);

@@ -211,7 +211,7 @@ static int fwd_impl(const void* q, const void* k, const void* v, void* out, floa
     if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out))
         return fail(MTFM_HTA_ERR_INVALID_ARG, "q, k, v, out must be 16-byte aligned");
     if (has_rt && !timestamps) return fail(MTFM_HTA_ERR_INVALID_ARG, "null pointer argument");
-    const int splits = pointwise ? 1 : forward_splits(dtype, layer, batch, max_hist, max_rt, max_targets, Hq, Hkv, head_dim);
+    const int splits = forward_splits(dtype, layer, batch, max_hist, max_rt, max_targets, Hq, Hkv, head_dim);
     const Workspace w = plan_workspace(dtype, 0, batch, total_q, Hq, has_rt, splits, head_dim);
     rc = check_workspace(w, workspace, workspace_bytes);
     if (rc != MTFM_HTA_OK) return rc;
@@ -349,7 +349,8 @@ size_t mtfm_hta_pw_workspace_bytes(int layer, int dtype, int is_bwd, int32_t bat
                                    int32_t max_hist, int32_t max_targets, int32_t Hq, int32_t Hkv, int32_t head_dim) {
     if (check_scalars(layer, dtype, batch, total_q, total_kv, max_hist, 0, max_targets, Hq, Hkv, head_dim) != MTFM_HTA_OK)
         return (size_t)-1;
-    return plan_workspace(dtype, is_bwd, batch, total_q, Hq, false).total;
+    const int splits = is_bwd ? 1 : forward_splits(dtype, layer, batch, max_hist, 0, max_targets, Hq, Hkv, head_dim);
+    return plan_workspace(dtype, is_bwd, batch, total_q, Hq, false, splits, head_dim).total;
 }
 
 int mtfm_hta_pw_fwd(const void* q, const void* k, const void* v, void* out, const int32_t* q_offsets,
@@ -377,7 +378,8 @@ size_t mtfm_hta_pw_workspace_bytes_rt(int layer, int dtype, int is_bwd, int32_t 
                                       int32_t head_dim) {
     if (check_scalars(layer, dtype, batch, total_q, total_kv, max_hist, max_rt, max_targets, Hq, Hkv, head_dim) != MTFM_HTA_OK)
         return (size_t)-1;
-    return plan_workspace(dtype, is_bwd, batch, total_q, Hq, true).total;
+    const int splits = is_bwd ? 1 : forward_splits(dtype, layer, batch, max_hist, max_rt, max_targets, Hq, Hkv, head_dim);
+    return plan_workspace(dtype, is_bwd, batch, total_q, Hq, true, splits, head_dim).total;
 }
 
 int mtfm_hta_pw_fwd_rt(const void* q, const void* k, const void* v, void* out, const int32_t* q_offsets,

@@ -37,10 +37,10 @@ constexpr float RESCALE_SLACK = 8.f;  // log2 units a row's logits may exceed it
 // the workspace; split 0 also takes the rows' own keys.  merge_splits_kernel combines the partial results.
 //
 // PW: the pointwise reading of phi2 -- weights norm * silu(scale s) on the same tiles and mask: no running maximum, no
-// row sum, no lse; the accumulator is scaled by norm at the store.  (Unsplit launches only.)
+// row sum, no lse; the accumulator is scaled by norm at the store.  With SPLIT the partial results are plain partial
+// sums, which the merge kernel adds up.
 template <int D, int RB, int NW, bool RT, bool SPLIT, bool PW = false>
 __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb, int n_hc, int tpg) {
-    static_assert(!(PW && SPLIT), "the pointwise variant is built for unsplit launches");
     using ST = KvStage<D, NW>;
     constexpr int NKS = D / 16, NDB = D / 32, NKB = BN / 32;
     static_assert(ST::BN == BN, "tile height");
@@ -279,7 +279,7 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb,
         const float lt = l[rb] + other_half(l[rb]);
         if (live && SPLIT) {
             // partial result of this split: rows normalised by their own sum (0 when the split saw no key: lse = -inf)
-            const float inv = lt > 0.f ? 1.f / lt : 0.f;
+            const float inv = PW ? p.norm : (lt > 0.f ? 1.f / lt : 0.f);
             float* op = p.o_part + (((int64_t)split * p.total_q + q_base + row) * p.Hq + h) * D;
 #pragma unroll
             for (int db = 0; db < NDB; db++)
@@ -290,7 +290,7 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb,
                     for (int j = 0; j < 4; j++) o4[j] = O[rb][db][4 * v4 + j] * inv;
                     *(floatx4*)(op + db * 32 + 8 * v4 + 4 * hf) = o4;
                 }
-            if (hf == 0)
+            if (!PW && hf == 0)
                 p.lse_part[((int64_t)split * p.Hq + h) * p.total_q + q_base + row] =
                     lt > 0.f ? (m[rb] + __builtin_amdgcn_logf(lt)) * LN2 : -INFINITY;
         } else if (live) {
@@ -312,6 +312,8 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb,
 
 // out = sum_s w_s O_s / sum_s w_s with w_s = exp(lse_s - max lse), lse = max lse + log sum_s w_s: the exact
 // combination of softmax results over disjoint key sets.  One thread per 4 features of a (row, head).
+// PW: the partial results are partial sums of non-normalised weights: out = sum_s O_s, no lse.
+template <bool PW>
 __global__ __launch_bounds__(256) void merge_splits_kernel(Params p) {
     const int64_t quads = p.d / 4;
     const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -325,23 +327,25 @@ __global__ __launch_bounds__(256) void merge_splits_kernel(Params p) {
     const float* op = p.o_part + (row * p.Hq + h) * p.d + 4 * c;
     const int64_t l_stride = (int64_t)p.Hq * p.total_q, o_stride = p.total_q * p.Hq * p.d;
     float mx = -INFINITY;
+    if constexpr (!PW) {
 #pragma unroll 8
-    for (int s = 0; s < p.n_splits; s++) mx = fmaxf(mx, lp[s * l_stride]);
+        for (int s = 0; s < p.n_splits; s++) mx = fmaxf(mx, lp[s * l_stride]);
+    }
     float sum = 0.f;
     floatx4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll 8
     for (int s = 0; s < p.n_splits; s++) {
-        const float w = __expf(lp[s * l_stride] - mx);
+        const float w = PW ? 1.f : __expf(lp[s * l_stride] - mx);
         const floatx4 o = *(const floatx4*)(op + s * o_stride);
         sum += w;
         acc += w * o;
     }
-    const float inv = 1.f / sum;
+    const float inv = PW ? 1.f : 1.f / sum;
     bf16x4 o4;
 #pragma unroll
     for (int j = 0; j < 4; j++) o4[j] = (__bf16)(acc[j] * inv);
     *(bf16x4*)((__bf16*)p.out + (row * p.Hq + h) * p.d + 4 * c) = o4;
-    if (c == 0) p.lse[(int64_t)h * p.total_q + row] = mx + __logf(sum);
+    if (!PW && c == 0) p.lse[(int64_t)h * p.total_q + row] = mx + __logf(sum);
 }
 
 int gcd(int a, int b) { return b == 0 ? a : gcd(b, a % b); }
@@ -365,10 +369,14 @@ Geometry geometry_of(int RB, int NW, int32_t batch, int32_t Hq, int32_t Hkv, int
 template <int D, int RB, int NW>
 hipError_t launch(const Params& p, hipStream_t s) {
     const bool split = p.n_splits > 1;
-    if (p.pointwise && split) return hipErrorInvalidValue;
-    auto kernel = p.pointwise ? (p.rt_len ? fwd_bf16_kernel<D, RB, NW, true, false, true> : fwd_bf16_kernel<D, RB, NW, false, false, true>)
-                  : p.rt_len  ? (split ? fwd_bf16_kernel<D, RB, NW, true, true> : fwd_bf16_kernel<D, RB, NW, true, false>)
-                              : (split ? fwd_bf16_kernel<D, RB, NW, false, true> : fwd_bf16_kernel<D, RB, NW, false, false>);
+    void (*kernel)(Params, int, int, int);
+    if (p.pointwise) {
+        kernel = p.rt_len ? (split ? fwd_bf16_kernel<D, RB, NW, true, true, true> : fwd_bf16_kernel<D, RB, NW, true, false, true>)
+                          : (split ? fwd_bf16_kernel<D, RB, NW, false, true, true> : fwd_bf16_kernel<D, RB, NW, false, false, true>);
+    } else {
+        kernel = p.rt_len ? (split ? fwd_bf16_kernel<D, RB, NW, true, true> : fwd_bf16_kernel<D, RB, NW, true, false>)
+                          : (split ? fwd_bf16_kernel<D, RB, NW, false, true> : fwd_bf16_kernel<D, RB, NW, false, false>);
+    }
     const int64_t rows = max_query_rows(p);
     if (rows <= 0) return hipSuccess;
     const Geometry g = geometry_of(RB, NW, p.batch, p.Hq, p.Hkv, rows);
@@ -379,7 +387,10 @@ hipError_t launch(const Params& p, hipStream_t s) {
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && split) {
         const int64_t threads = p.total_q * p.Hq * (p.d / 4);
-        hipLaunchKernelGGL(merge_splits_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, p);
+        if (p.pointwise)
+            hipLaunchKernelGGL(merge_splits_kernel<true>, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, p);
+        else
+            hipLaunchKernelGGL(merge_splits_kernel<false>, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, p);
         e = hipGetLastError();
     }
     return e;

@@ -147,8 +147,17 @@ def test_large_logits_and_unit_norm():
     check(c, norm=1.0, compare=close_on_tensor_scale)
 
 
-def test_a_small_batch_is_not_split_and_needs_no_saved_state():
-    c = inputs.make_case(inputs.CONFIGS["I1"])
+@pytest.mark.parametrize("name", ["I1", "I2", "I3", "I2_RT"])
+def test_inference_shapes_split_the_keys(name):
+    """A few requests: the forward pass splits the keys and adds up the partial sums (the backward pass is unsplit)."""
+    c = inputs.make_case(inputs.CONFIGS[name])
     b = device_batch(c, norm_of(c))
-    assert b.fwd_ws is not None and b.fwd_ws.numel() == 512   # schedule region only: no partial results
+    assert b.fwd_ws is not None and b.fwd_ws.numel() > 4096   # partial results in the workspace
+    check(c)
+
+
+def test_split_edge_batch():
+    # short users next to a long one: splits that see no key, less than a tile, exactly two tiles
+    c = inputs.make_case(inputs.custom_config("pw_split", TARGET, [2048, 0, 1, 63, 128, 65, 1000, 64],
+                                              [16, 5, 1, 33, 64, 2, 70, 0], 8, 2, 64, seed=56))
     check(c)

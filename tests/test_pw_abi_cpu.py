@@ -19,9 +19,11 @@ def test_library_exports_every_declared_symbol():
         assert getattr(lib, n) is not None
 
 
-def test_workspace_never_holds_split_partials():
-    # the same few users for which the softmax forward pass splits its keys: here only the schedule region
-    assert hta_pw.mtfm_hta_pw_workspace_bytes(hta.LAYER_FULL, hta.BF16, False, 4, 1000, 1000, 512, 64, 8, 2, 64) == 512
+def test_workspace_bytes_is_host_arithmetic():
+    # a few users: the forward pass splits its keys exactly as the softmax variant does, same workspace
+    assert (hta_pw.mtfm_hta_pw_workspace_bytes(hta.LAYER_FULL, hta.BF16, False, 4, 1000, 1000, 512, 64, 8, 2, 64) ==
+            hta.mtfm_hta_workspace_bytes(hta.LAYER_FULL, hta.BF16, False, 4, 1000, 1000, 512, 64, 8, 2, 64))
+    assert hta_pw.mtfm_hta_pw_workspace_bytes(hta.LAYER_FULL, hta.BF16, False, 300, 100000, 100000, 512, 64, 8, 2, 64) == 256 + 1280
     n = hta_pw.mtfm_hta_pw_workspace_bytes(hta.LAYER_FULL, hta.BF16, True, 4, 1000, 1000, 512, 64, 8, 2, 64)
     assert n >= 512 + 2 * 1000 * 8 * 4 and n % 256 == 0
     assert hta_pw.mtfm_hta_pw_workspace_bytes(hta.LAYER_FULL, hta.FP32, True, 4, 1000, 1000, 512, 64, 8, 2, 16) == 0
@@ -33,7 +35,7 @@ def test_workspace_never_holds_split_partials():
     (dict(scale=0.0), hta.ERR_INVALID_ARG), (dict(norm=0.0), hta.ERR_INVALID_ARG),
     (dict(norm=float("inf")), hta.ERR_INVALID_ARG), (dict(norm=float("nan")), hta.ERR_INVALID_ARG),
     (dict(d=48), hta.ERR_UNSUPPORTED), (dict(Hkv=3), hta.ERR_INVALID_ARG), (dict(q=None), hta.ERR_INVALID_ARG),
-    (dict(ws_bytes=0), hta.ERR_WORKSPACE),
+    (dict(ws_bytes=511), hta.ERR_WORKSPACE),
 ])
 def test_forward_rejects_bad_arguments_without_launching(kw, status):
     lib = hta_pw.load_library()
