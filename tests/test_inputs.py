@@ -65,3 +65,28 @@ def test_visible_pairs_formula():
     nt = np.array([8, 8], np.int32)
     assert inputs.visible_pairs(hl, nt, 4, inputs.LAYER_FULL) == 26176
     assert inputs.visible_pairs(hl, nt, 4, inputs.LAYER_TARGET) == 4 * (328 + 520)
+
+
+def test_gln_case_is_reproducible_and_groups_differ_in_distribution():
+    a = inputs.make_gln_case("g", 4000, 64, 4, dtype="bf16", gated=True, seed=3)
+    b = inputs.make_gln_case("g", 4000, 64, 4, dtype="bf16", gated=True, seed=3)
+    assert np.array_equal(a.x, b.x) and np.array_equal(a.group_id, b.group_id) and np.array_equal(a.gamma, b.gamma)
+    assert a.x.shape == (4000, 64) and a.gate.shape == a.x.shape and a.gamma.shape == (4, 64)
+    assert a.group_id.dtype == np.int32 and a.group_id.min() == 0 and a.group_id.max() == 3
+    counts = np.bincount(a.group_id, minlength=4)
+    assert counts.min() > 800                                   # uniform over the groups
+    # every value survives a bf16 round trip, and the groups' feature means / spreads differ (what the groups are for)
+    assert np.array_equal(inputs.bf16_bits_to_f32(inputs.f32_to_bf16_bits(a.x)).reshape(a.x.shape), a.x)
+    means = np.array([a.x[a.group_id == g].mean() for g in range(4)])
+    stds = np.array([a.x[a.group_id == g].std() for g in range(4)])
+    assert np.ptp(means) > 0.2 and np.ptp(stds) > 0.2
+    assert inputs.make_gln_case("g", 10, 8, 2, gated=False).gate is None
+
+
+def test_inference_configs_are_small_target_layer_batches():
+    for name in ("I1", "I2", "I3", "I2_RT"):
+        cfg = inputs.CONFIGS[name]
+        assert cfg.layer == inputs.LAYER_TARGET and cfg.batch <= 8 and cfg.dtype == "bf16"
+    c = inputs.make_case(inputs.CONFIGS["I2_RT"])
+    assert c.total_q == int(c.n_targets.sum()) and c.rt_len is not None
+    assert c.total_kv == int((c.hist_len + c.rt_len + c.n_targets).sum())
