@@ -80,6 +80,8 @@ SHAPES = [
     (1000, 512, 8, "fp32", True),
     (333, 200, 5, "fp32", False),
     (9000, 1024, 8, "fp32", True),    # the full LDS table (8 x 1024), several passes of the grid
+    (300, 2048, 4, "fp32", True),     # the widest row in float32 (the instantiation with the largest register need)
+    (260, 1536, 5, "fp32", False),
     (1, 8, 1, "fp32", False),         # the smallest call
 ]
 
