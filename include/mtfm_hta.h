@@ -68,7 +68,7 @@ enum { MTFM_HTA_LAYER_FULL = 0, MTFM_HTA_LAYER_TARGET = 1 };
  * The bf16 path keeps there what it builds on the device at the start of every call -- the work
  * counters of its persistent kernels and the user schedule (users ordered by decreasing number of
  * attention tiles, from hist_len / n_targets) -- and, for the backward pass, two float32 values per
- * (query head, query row): -delta = -<dout, out> and -lse log2(e).
+ * (query head, query row): -delta = -<dout, out> and -lse / softmax_scale.
  * A forward call on so few users that (user, kv head, row tile) items cannot give every compute unit a workgroup
  * (a handful of requests at inference; decided from batch, the max_* bounds and the head shape alone) splits the keys
  * of each item over several workgroups; the workspace then also holds their partial results, float32

@@ -52,7 +52,7 @@ struct Workspace {
 
 // Layout of the caller's workspace (bf16 path; the fp32 debug path needs none):
 //   work counters (256 bytes) and order [batch] int32, users by decreasing tile count; both rebuilt by every call
-//   -delta and -lse log2(e), [Hq][total_q] f32 each, the latter followed by one sentinel element   backward only
+//   -delta and -lse/scale, [Hq][total_q] f32 each, the latter followed by one sentinel element   backward only
 //   with real-time tokens (both dtypes): lim [total_q] int32, the per-row limits of mask rule 2, rebuilt by every call
 //   forward pass split over the keys (`splits` > 1: few requests, decided from the host-known bounds alone):
 //   partial outputs [splits][total_q][Hq][d] f32 and their logsumexps [splits][Hq][total_q] f32

@@ -13,7 +13,7 @@
 //      the query row on the lane, so lse and delta are one register each and dS^T in accumulator layout
 //      is directly the k-operand of dQ^T = K^T dS^T.  The self key of a target row is one extra term
 //      in the epilogue.  dq is written once.  delta_i = <dO_i, O_i> is formed here, from the dO fragments
-//      the wave holds anyway, and left (negated, with -lse log2 e) in the workspace for the third kernel.
+//      the wave holds anyway, and left (negated, with -lse/scale) in the workspace for the third kernel.
 //   3. bwd_dkdv: key-stationary: a wave owns 32 history keys (K, V fragments and the dK, dV accumulators
 //      stay in registers for the whole kernel), the workgroup streams (head, 32-row block) tiles of Q
 //      and dO through LDS, shared by its waves.  S = Q K^T and dP = dO V^T have the key on the lane, so
@@ -131,7 +131,7 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(Params p, int hpb, i
     __shared__ __attribute__((aligned(1024))) unsigned char smem[NSTAGE * ST::BYTES];
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
-    // behind the -lse log2(e) array: what the S accumulators of rows that do not exist start from in the dK/dV pass
+    // behind the -lse/scale array: what the S accumulators of rows that do not exist start from in the dK/dV pass
     if (blockIdx.x == 0 && tid == 0) p.neg_lse_s[(int64_t)p.Hq * p.total_q] = -1e30f;
     const WorkItem w = decode_work(blockIdx.x, p.batch * p.Hkv * n_hc, p.Hkv * n_hc, tpg);
     if (!w.valid) return;
@@ -192,7 +192,7 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(Params p, int hpb, i
         // every (row, head) belongs to exactly one wave of this kernel: it leaves the row statistics for the dK/dV pass
         if (row_live && hf == 0) {
             p.neg_delta[stat] = -delta;
-            p.neg_lse_s[stat] = -lse * LOG2E;
+            p.neg_lse_s[stat] = -lse / p.scale;
         }
     }
     floatx16 dQ[RB][NDB];  // dQ^T: [d (registers)][row (lanes)]
@@ -360,7 +360,7 @@ struct DkdvSmem {
     static constexpr int UPI = 2;      // (head, 32-row block) units per loop iteration, i.e. per workgroup barrier
     static constexpr int NSTAGE = 3;   // iterations resident in LDS: one being consumed, two in flight
     static constexpr int TILE = 32 * D;                 // one unpadded, swizzled 32-row tile (elements)
-    // Q, dO, -lse log2(e)[32], -delta[32]; with real-time tokens also the rows' limits, int[32] (written twice)
+    // Q, dO, -lse/scale[32], -delta[32]; with real-time tokens also the rows' limits, int[32] (written twice)
     static constexpr size_t UNIT_BYTES = (size_t)2 * TILE * 2 + 2 * 32 * sizeof(float) + (RT ? 256 : 0);
     static constexpr size_t STAGE_BYTES = UPI * UNIT_BYTES;
     static constexpr size_t BYTES = NSTAGE * STAGE_BYTES;
@@ -449,12 +449,6 @@ __global__ __launch_bounds__(NW * 64, D > 64 ? 1 : 2) void bwd_dkdv_kernel(Param
         for (int ks = 0; ks < NKS; ks++) {
             kf[ks] = *(const bf16x8*)((const __bf16*)p.k + off + ks * 16);
             vf[ks] = *(const bf16x8*)((const __bf16*)p.v + off + ks * 16);
-            // The softmax weights are exp2(log2(e) (scale s - lse)): the factor log2(e) scale goes into the stationary
-            // K fragments once per work item instead of into every score (dK is formed from Q and dS, not from these).
-            if constexpr (!PW) {
-#pragma unroll
-                for (int j = 0; j < 8; j++) kf[ks][j] = (__bf16)((float)kf[ks][j] * c2);
-            }
         }
     }
     floatx16 dK[NDB], dV[NDB];  // [key (registers)][d (lanes)]
@@ -515,8 +509,8 @@ __global__ __launch_bounds__(NW * 64, D > 64 ? 1 : 2) void bwd_dkdv_kernel(Param
                     copy16_global_to_lds_at((const __bf16*)p.q + off, dst);
                     copy16_global_to_lds_at((const __bf16*)p.dout + off, dst + (uint32_t)SM::TILE * 2u);
                 }
-                // A row that does not exist starts from the sentinel behind the -lse log2(e) array, a huge negative
-                // number: its weights P = exp2(that) are exactly 0, and so is all it would add to dK and dV.
+                // A row that does not exist starts from the sentinel behind the -lse/scale array, a huge negative
+                // number: its weights P = exp(scale * that) are exactly 0, and so is all it would add to dK and dV.
                 if (wave_u == uu) {
                     int row = row0 + l32;
                     const bool dead = past || row >= n_rows;
@@ -568,7 +562,7 @@ __global__ __launch_bounds__(NW * 64, D > 64 ? 1 : 2) void bwd_dkdv_kernel(Param
             o.qa[ks] = *(const bf16x8*)(Qs + nat_off[ks]);
             o.da[ks] = *(const bf16x8*)(dOs + nat_off[ks]);
         }
-        // accumulators start from -lse log2(e) and -delta of their rows (registers 4j..4j+3 hold rows 8j+4hf .. +3)
+        // accumulators start from -lse/scale and -delta of their rows (registers 4j..4j+3 hold rows 8j+4hf .. +3)
         floatx4 l4[4], d4[4];
 #pragma unroll
         for (int j = 0; j < 4; j++) {
@@ -585,7 +579,7 @@ __global__ __launch_bounds__(NW * 64, D > 64 ? 1 : 2) void bwd_dkdv_kernel(Param
     auto scores = [&](Operands& o) {
 #pragma unroll
         for (int ks = 0; ks < NKS; ks++) {
-            o.S = mfma32(o.qa[ks], kf[ks], o.S);     // log2(e) (scale S - lse): the K fragments carry the factor
+            o.S = mfma32(o.qa[ks], kf[ks], o.S);     // S - lse/scale
             o.dP = mfma32(o.da[ks], vf[ks], o.dP);   // dP - delta
         }
     };
@@ -641,7 +635,7 @@ __global__ __launch_bounds__(NW * 64, D > 64 ? 1 : 2) void bwd_dkdv_kernel(Param
         }
 #pragma unroll
         for (int v = 0; v < 16; v++) {
-            float pw = fast_exp2(o.S[v]);
+            float pw = fast_exp2(o.S[v] * c2);
             if constexpr (MASKED && RT) {
                 const int key = kw + l32;
                 const bool vis = key < limv[v] || (key_live && self_row == 8 * (v / 4) + 4 * hf + (v % 4));

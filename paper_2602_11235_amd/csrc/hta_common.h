@@ -32,7 +32,7 @@ struct Params {
     int32_t layer;        // 0 full (queries = all tokens), 1 target (queries = target tokens)
     // carved out of the caller's workspace (bwd)
     float* neg_delta;     // [Hq][total_q]   -<dout_i, out_i>
-    float* neg_lse_s;     // [Hq][total_q]   -lse_i log2(e): what the S accumulators of the dK/dV pass start from
+    float* neg_lse_s;     // [Hq][total_q]   -lse_i / scale: what the S accumulators of the dK/dV pass start from
     const int32_t* order; // [batch] users by decreasing tile count (bf16 path), or null = identity
     int32_t* queue;       // [N_XCD] work counters of the kernel being launched (bf16 path), zero when it starts
     // real-time tokens (mask rule 2); all null / 0 for samples of history + target tokens only
