@@ -136,8 +136,8 @@ MTFM_HTA_API int mtfm_hta_validate_host(const int32_t* q_offsets, const int32_t*
                            int32_t max_hist, int32_t max_targets, int layer);
 
 /*
- * Samples with real-time tokens (mask rule 2 of the dynamic mask, Section 3.2.2: "the R-tokens are visible only to
- * tokens with later timestamps").  The K/V rows of user b are then hist_len[b] history tokens, rt_len[b] real-time
+ * Samples with real-time tokens (mask rule 2 of the dynamic mask, Section 3.2.2: a real-time key may be attended to
+ * only by queries whose timestamp is later than its own).  The K/V rows of user b are then hist_len[b] history tokens, rt_len[b] real-time
  * tokens, n_targets[b] target tokens, in this order (X = (H; R; T), Section 3.2.1); the queries of a full layer are
  * all of them, those of a target layer the target tokens.  Visibility of key j for query i:
  *   history key: always (rule 1);   target key: j == i (rule 3);

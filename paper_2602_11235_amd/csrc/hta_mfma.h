@@ -128,19 +128,19 @@ __device__ inline int swizzle(int row) {
 // lds_wave_base[16 i .. 16 i + 15] with the 16 bytes at its own global address (lds_wave_base must be the same
 // for all lanes).  Completion is tracked by the wave's vector-memory counter like any load, and is the caller's
 // business (wait_vmem_outstanding): the copy is issued from inline assembly precisely so that the compiler does
-// not drain it before every later LDS read.  Its own vmcnt waits for ordinary loads ignore these copies, which
+// not drain it before every later LDS read.  The statement overwrites M0 and says so in its clobber list.  Its own vmcnt waits for ordinary loads ignore these copies, which
 // only makes them wait longer than needed, never less (the counter retires in issue order).
 __device__ inline void copy16_global_to_lds(const void* global_lane_ptr, void* lds_wave_base) {
     const uint32_t base =
         __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)lds_wave_base);
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(base), "v"(global_lane_ptr) : "memory");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(base), "v"(global_lane_ptr) : "memory", "m0");
 }
 
 // Same for 4 bytes per lane: lane i writes lds_wave_base[4 i .. 4 i + 3].
 __device__ inline void copy4_global_to_lds(const void* global_lane_ptr, void* lds_wave_base) {
     const uint32_t base =
         __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)lds_wave_base);
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" : : "s"(base), "v"(global_lane_ptr) : "memory");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" : : "s"(base), "v"(global_lane_ptr) : "memory", "m0");
 }
 
 // The same copies with the LDS destination given as a byte address inside LDS (wave-uniform), which spares the
@@ -148,17 +148,17 @@ __device__ inline void copy4_global_to_lds(const void* global_lane_ptr, void* ld
 __device__ inline uint32_t lds_address(const void* p) { return (uint32_t)(uintptr_t)(HTA_LDS const void*)p; }
 
 __device__ inline void copy16_global_to_lds_at(const void* global_lane_ptr, uint32_t lds_wave_addr) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_wave_addr), "v"(global_lane_ptr) : "memory");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_wave_addr), "v"(global_lane_ptr) : "memory", "m0");
 }
 
 __device__ inline void copy4_global_to_lds_at(const void* global_lane_ptr, uint32_t lds_wave_addr) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" : : "s"(lds_wave_addr), "v"(global_lane_ptr) : "memory");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" : : "s"(lds_wave_addr), "v"(global_lane_ptr) : "memory", "m0");
 }
 
 // 16-byte copy whose global address is a wave-uniform base plus a per-lane unsigned byte offset: no address
 // arithmetic on the vector unit at all when the per-lane offsets are loop-invariant.
 __device__ inline void copy16_global_to_lds_at(const void* uniform_base, uint32_t lane_byte_offset, uint32_t lds_wave_addr) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_wave_addr), "v"(lane_byte_offset), "s"(uniform_base) : "memory");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_wave_addr), "v"(lane_byte_offset), "s"(uniform_base) : "memory", "m0");
 }
 
 // wait until at most N vector-memory operations of this wave are still outstanding (N < 64)

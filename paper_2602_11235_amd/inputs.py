@@ -298,18 +298,6 @@ def user_rows(offsets: np.ndarray, users) -> np.ndarray:
     return np.concatenate([np.arange(offsets[u], offsets[u + 1]) for u in users])
 
 
-def visible_pairs(hist_len: np.ndarray, n_targets: np.ndarray, Hq: int, layer: int) -> int:
-    """Number of (query, key) pairs the hybrid mask leaves visible, summed over heads: per user
-    L^2 + T*L + T for a full layer and T*L + T for a target layer (the N^2 vs N*L_T terms of the
-    complexity statement in Section 3.2.2)."""
-    L = hist_len.astype(np.int64)
-    T = n_targets.astype(np.int64)
-    per = T * L + T
-    if layer == LAYER_FULL:
-        per = per + L * L
-    return int(Hq * per.sum())
-
-
 def take_kv_group(case: Case, g: int) -> Case:
     """The sub-problem of one key/value head and the r query heads that read it (heads of different kv
     groups never interact, so a result on the slice is the result for those heads)."""
@@ -322,24 +310,6 @@ def take_kv_group(case: Case, g: int) -> Case:
                 np.ascontiguousarray(case.v[:, g:g + 1]),
                 None if case.dout is None else np.ascontiguousarray(case.dout[:, hs]), case.scale, case.rt_len,
                 case.timestamps)
-
-
-def visible_pairs_of(case: Case) -> int:
-    """visible_pairs for a batch that may carry real-time tokens: under rule 2 a real-time key is visible to the
-    queries with a strictly later timestamp and to its own token."""
-    cfg = case.cfg
-    if case.rt_len is None:
-        return visible_pairs(case.hist_len, case.n_targets, cfg.Hq, cfg.layer)
-    total = 0
-    for b in range(case.batch):
-        L, R, T = int(case.hist_len[b]), int(case.rt_len[b]), int(case.n_targets[b])
-        ts = case.timestamps[case.kv_offsets[b]:case.kv_offsets[b + 1]].astype(np.int64)
-        first = 0 if cfg.layer == LAYER_FULL else L + R
-        rows_ts = ts[first:]
-        total += rows_ts.shape[0] * L                                               # rule 1
-        total += int(np.searchsorted(ts[L:L + R], rows_ts, side="left").sum())       # rule 2: strictly earlier keys
-        total += (R if cfg.layer == LAYER_FULL else 0) + T                           # own keys
-    return int(cfg.Hq * total)
 
 
 # ----------------------------------------------------------------------------- group layer normalization

@@ -1,6 +1,7 @@
 """The seeded generators: reproducible, independent of chunking, with the advertised shapes."""
 import numpy as np
 
+import bench
 from paper_2602_11235_amd import inputs
 
 
@@ -63,8 +64,8 @@ def test_target_layer_offsets_and_subset():
 def test_visible_pairs_formula():
     hl = np.array([40, 64], np.int32)
     nt = np.array([8, 8], np.int32)
-    assert inputs.visible_pairs(hl, nt, 4, inputs.LAYER_FULL) == 26176
-    assert inputs.visible_pairs(hl, nt, 4, inputs.LAYER_TARGET) == 4 * (328 + 520)
+    assert bench.visible_pairs(hl, nt, 4, inputs.LAYER_FULL) == 26176
+    assert bench.visible_pairs(hl, nt, 4, inputs.LAYER_TARGET) == 4 * (328 + 520)
 
 
 def test_gln_case_is_reproducible_and_groups_differ_in_distribution():

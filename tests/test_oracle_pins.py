@@ -11,6 +11,7 @@ import pytest
 import torch
 
 from oracle import hta_oracle as O
+import bench
 from paper_2602_11235_amd import inputs
 
 FULL, TARGET = inputs.LAYER_FULL, inputs.LAYER_TARGET
@@ -130,7 +131,7 @@ def test_pair_counts_match_complexity_statement():
             total_full += np.count_nonzero(P)
             Pt = O.probs(c.q[c.q_offsets[b] + L:], c.k, 0, c.kv_offsets[b], L, T, h, c.scale, TARGET)
             assert np.count_nonzero(Pt) == target_pairs
-    assert total_full == 26176 == inputs.visible_pairs(c.hist_len, c.n_targets, c.cfg.Hq, FULL)
+    assert total_full == 26176 == bench.visible_pairs(c.hist_len, c.n_targets, c.cfg.Hq, FULL)
 
 
 # ------------------------------------------------------------------ brute force

@@ -9,6 +9,7 @@ import pytest
 import torch
 
 from oracle import hta_oracle as O
+import bench
 from paper_2602_11235_amd import inputs
 
 FULL, TARGET = inputs.LAYER_FULL, inputs.LAYER_TARGET
@@ -240,7 +241,7 @@ def test_visible_pair_count_matches_the_mask():
         ks, ke = int(case.kv_offsets[b]), int(case.kv_offsets[b + 1])
         count += int(dense_mask(int(case.hist_len[b]), int(case.rt_len[b]), int(case.n_targets[b]),
                                 case.timestamps[ks:ke]).sum())
-    assert inputs.visible_pairs_of(case) == case.cfg.Hq * count
+    assert bench.visible_pairs_of(case) == case.cfg.Hq * count
     for h in range(case.cfg.Hq):
         p = O.probs(case.q, case.k, 0, 0, int(case.hist_len[0]), int(case.n_targets[0]), h, case.scale, FULL,
                     rt_len=int(case.rt_len[0]), timestamps=case.timestamps)
