@@ -62,14 +62,18 @@ def mtfm_gln_validate_host(group_id: torch.Tensor, n_groups: int) -> None:
 
 def mtfm_gln_fwd(x: torch.Tensor, group_id: torch.Tensor, gamma: torch.Tensor, beta: torch.Tensor, eps: float,
                  gate: Optional[torch.Tensor] = None, y: Optional[torch.Tensor] = None,
-                 save_stats: bool = True) -> Tuple[torch.Tensor, Optional[torch.Tensor], Optional[torch.Tensor]]:
-    """y = GLN(x) (times gate); returns (y, mean, rstd), the statistics being None when save_stats is False."""
+                 save_stats: bool = True, stats=None) -> Tuple[torch.Tensor, Optional[torch.Tensor], Optional[torch.Tensor]]:
+    """y = GLN(x) (times gate); returns (y, mean, rstd), the statistics being None when save_stats is False.
+    `stats` may hold preallocated (mean, rstd) tensors."""
     lib = load_library()
     n, d = x.shape
     if y is None:
         y = torch.empty_like(x)
-    mean = torch.empty(n, dtype=torch.float32, device=x.device) if save_stats else None
-    rstd = torch.empty(n, dtype=torch.float32, device=x.device) if save_stats else None
+    if stats is not None:
+        mean, rstd = stats
+    else:
+        mean = torch.empty(n, dtype=torch.float32, device=x.device) if save_stats else None
+        rstd = torch.empty(n, dtype=torch.float32, device=x.device) if save_stats else None
     _check(lib.mtfm_gln_fwd(hta._ptr(x), hta._ptr(gate), hta._ptr(group_id), hta._ptr(gamma), hta._ptr(beta),
                             hta._ptr(y), hta._ptr(mean), hta._ptr(rstd), n, d, gamma.shape[0], eps, _dtype_code(x),
                             _stream()))

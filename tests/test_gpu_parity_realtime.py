@@ -42,12 +42,12 @@ def test_c2_rt_full_batch():
 
 def test_c3_rt_sampled_users():
     c = inputs.make_case(inputs.CONFIGS["C3_RT"])
-    check_case(c, with_bwd=True, users=pick_users(c, 2))
+    check_case(c, with_bwd=True, users=pick_users(c, 12))
 
 
 def test_c4_rt_target_layer_sampled_users():
     c = inputs.make_case(inputs.CONFIGS["C4_RT"])
-    check_case(c, with_bwd=True, users=[0, 63, 127])
+    check_case(c, with_bwd=True, users=sorted(set(pick_users(c, 12)) | {0, 63, 127}))
 
 
 def test_zero_realtime_tokens_equal_the_plain_entry_points_bitwise():
