@@ -26,9 +26,9 @@
  *
  * Pointers.  Every data pointer (q,k,v,out,lse,dout,dq,dk,dv, the four int32 arrays, workspace) is a
  * DEVICE pointer; `stream` is a hipStream_t passed as void* (NULL = the default stream).  The caller
- * owns all buffers.  The library never allocates or frees device memory, never copies to the host and
- * never synchronises: a call validates its scalar arguments on the host, enqueues kernels on `stream`
- * and returns.  Device-resident arrays are not validated (that would need a device-to-host copy);
+ * owns all buffers.  The functions declared in this header never allocate or free device memory, never copy
+ * to the host and never synchronise: a call validates its scalar arguments on the host, enqueues kernels on
+ * `stream` and returns.  (The optional instrumentation of mtfm_hta_timing.h is separate and does block.)  Device-resident arrays are not validated (that would need a device-to-host copy);
  * they must satisfy the layout above, and hist_len[b] <= max_hist, n_targets[b] <= max_targets.
  *
  * Errors.  Every entry point returning int returns an mtfm_hta_status; on a non-zero status nothing
@@ -170,23 +170,6 @@ MTFM_HTA_API int mtfm_hta_bwd_rt(const void* dout, const void* q, const void* k,
 MTFM_HTA_API int mtfm_hta_validate_host_rt(const int32_t* q_offsets, const int32_t* kv_offsets, const int32_t* hist_len,
                  const int32_t* rt_len, const int32_t* n_targets, const int32_t* timestamps, int32_t batch,
                  int64_t total_q, int64_t total_kv, int32_t max_hist, int32_t max_rt, int32_t max_targets, int layer);
-
-/*
- * Optional per-kernel timing (benchmarks, profiling).  mtfm_hta_timing_enable(slots) creates `slots`
- * HIP event pairs per kernel kind (slots <= 0: destroy them and switch timing off, the default).  While
- * on, every call records an event pair on its stream around each kernel it enqueues, into a ring of
- * `slots` entries per kind.  mtfm_hta_timing_read() waits for the recorded events of one kind (this is
- * the only blocking call of the library), writes up to `capacity` durations in milliseconds to the HOST
- * array `ms`, oldest first, empties that ring and returns how many it wrote (or a negative status).
- * Process-wide state; not meant to be toggled while another thread is inside a call.
- */
-enum { MTFM_HTA_KERNEL_FWD = 0,      /* forward attention kernel */
-       MTFM_HTA_KERNEL_BWD_SELF = 1, /* dk/dv of the target tokens' own keys */
-       MTFM_HTA_KERNEL_BWD_DQ = 2,   /* dq (row-stationary pass; the whole backward of the fp32 path) */
-       MTFM_HTA_KERNEL_BWD_DKDV = 3, /* dk, dv of the history keys (key-stationary pass) */
-       MTFM_HTA_N_KERNELS = 7        /* kinds 4..6 belong to mtfm_gln.h */ };
-MTFM_HTA_API int mtfm_hta_timing_enable(int slots);
-MTFM_HTA_API int mtfm_hta_timing_read(int kernel, float* ms, int capacity);
 
 /* Message for the calling thread's most recent non-OK status ("" if none).  Points to thread-local
  * static storage owned by the library: do not free; valid until the thread's next failing call. */

@@ -26,6 +26,7 @@
 // under the hybrid mask.  Every transposed operand (K^T, Q^T, dO^T) is produced by the LDS transpose
 // read from a row-major tile; nothing is transposed when staged.
 #include "../../include/mtfm_hta.h"
+#include "../../include/mtfm_hta_timing.h"
 #include "hta_common.h"
 #include "hta_mfma.h"
 #include "hta_tiles.h"

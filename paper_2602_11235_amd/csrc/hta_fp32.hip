@@ -8,6 +8,7 @@
 // the visible keys of a row are the list [0, lead) followed by at most one more entry, `tok` itself, with
 // lead = L_b without real-time tokens and the precomputed per-row limit otherwise.
 #include "../../include/mtfm_hta.h"
+#include "../../include/mtfm_hta_timing.h"
 #include "hta_common.h"
 
 namespace hta {

@@ -16,6 +16,7 @@
 // directly the B operand of O^T = V^T P^T.  V stays row-major in LDS and is read through the LDS
 // transpose read.
 #include "../../include/mtfm_hta.h"
+#include "../../include/mtfm_hta_timing.h"
 #include "hta_common.h"
 #include "hta_mfma.h"
 #include "hta_tiles.h"

@@ -1,6 +1,7 @@
 // Optional per-kernel timing with HIP events recorded on the caller's stream, around each kernel
 // the library enqueues.  Off by default: when off, the hooks are two predictable branches.
 #include "../../include/mtfm_hta.h"
+#include "../../include/mtfm_hta_timing.h"
 #include "hta_common.h"
 
 #include <mutex>

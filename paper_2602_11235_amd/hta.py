@@ -1,4 +1,4 @@
-"""Thin ctypes binding of libmtfm_hta.so (C ABI declared in include/mtfm_hta.h).
+"""Thin ctypes binding of libmtfm_hta.so (C ABI declared in include/mtfm_hta.h; timing hooks in mtfm_hta_timing.h).
 
 Argument marshalling only: every step of the attention runs in the library's HIP kernels.
 PyTorch appears here for device memory and streams and nothing else.  If the shared library is

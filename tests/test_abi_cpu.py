@@ -13,7 +13,8 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def _declared_symbols():
-    text = open(os.path.join(ROOT, "include", "mtfm_hta.h")).read()
+    # the attention interface and the optional timing instrumentation (a header of its own)
+    text = "".join(open(os.path.join(ROOT, "include", h)).read() for h in ("mtfm_hta.h", "mtfm_hta_timing.h"))
     return sorted(set(re.findall(r"MTFM_HTA_API[^;(]*?\b(mtfm_hta_\w+)\s*\(", text)))
 
 
