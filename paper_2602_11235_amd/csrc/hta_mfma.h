@@ -128,7 +128,9 @@ __device__ inline int swizzle(int row) {
 // lds_wave_base[16 i .. 16 i + 15] with the 16 bytes at its own global address (lds_wave_base must be the same
 // for all lanes).  Completion is tracked by the wave's vector-memory counter like any load, and is the caller's
 // business (wait_vmem_outstanding): the copy is issued from inline assembly precisely so that the compiler does
-// not drain it before every later LDS read.  The statement overwrites M0 and says so in its clobber list.  Its own vmcnt waits for ordinary loads ignore these copies, which
+// not drain it before every later LDS read.  The statement overwrites M0 and says so in its clobber list:
+// the compiler reserves M0 for itself and sets it right before each use of its own, but its pass that merges equal M0
+// initialisations has to see that one was destroyed in between.  Its own vmcnt waits for ordinary loads ignore these copies, which
 // only makes them wait longer than needed, never less (the counter retires in issue order).
 __device__ inline void copy16_global_to_lds(const void* global_lane_ptr, void* lds_wave_base) {
     const uint32_t base =

@@ -312,6 +312,17 @@ def take_kv_group(case: Case, g: int) -> Case:
                 case.timestamps)
 
 
+def repeat_kv_heads(case: Case) -> Case:
+    """The same batch with one key/value head per query head: kv head g = h / r copied for each of its r query heads
+    (consecutive query heads share a kv head).  A rearrangement of the data only."""
+    cfg = case.cfg
+    r = cfg.Hq // cfg.Hkv
+    sub = dataclasses.replace(cfg, name=f"{cfg.name}_mha", Hkv=cfg.Hq)
+    return Case(sub, case.hist_len, case.n_targets, case.kv_offsets, case.q_offsets, case.q,
+                np.repeat(case.k, r, axis=1), np.repeat(case.v, r, axis=1), case.dout, case.scale, case.rt_len,
+                case.timestamps)
+
+
 # ----------------------------------------------------------------------------- group layer normalization
 @dataclasses.dataclass
 class GlnCase:

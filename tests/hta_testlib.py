@@ -42,18 +42,34 @@ def host(t: torch.Tensor) -> np.ndarray:
     return t.detach().float().cpu().numpy().astype(np.float64)
 
 
-def oracle_all(case: inputs.Case, with_bwd: bool):
+def oracle_all(case: inputs.Case, with_bwd: bool, per_head: bool = False):
+    """The oracle's results for `case`.
+
+    per_head: for users whose history is so long that one (user, kv head) unit of the oracle's backward pass -- it runs
+    one thread per such unit -- would take minutes.  The oracle is then run on the equivalent multi-head problem, every
+    query head with a copy of its kv head (grouped-query attention equals multi-head attention on consecutively
+    repeated K/V: one of the oracle's pins), which gives it r times as many units to run side by side; out, lse and dq
+    are the same, and dk/dv of a kv head are the sums of the per-head results over its r query heads."""
     layer = case.cfg.layer
-    rt = dict(rt_len=case.rt_len, timestamps=case.timestamps)
-    out, lse = O.forward(case.q, case.k, case.v, case.q_offsets, case.kv_offsets, case.hist_len, case.n_targets,
-                         case.scale, layer, **rt)
+    run = inputs.repeat_kv_heads(case) if per_head else case
+    rt = dict(rt_len=run.rt_len, timestamps=run.timestamps)
+    out, lse = O.forward(run.q, run.k, run.v, run.q_offsets, run.kv_offsets, run.hist_len, run.n_targets,
+                         run.scale, layer, **rt)
     if not with_bwd:
         return out, lse
     # the backward is fed the *oracle's* forward results: the GPU backward is checked against the exact
     # gradient, not against a gradient contaminated by its own forward rounding
-    dq, dk, dv = O.backward(case.dout, case.q, case.k, case.v, out, lse, case.q_offsets, case.kv_offsets,
-                            case.hist_len, case.n_targets, case.scale, layer, **rt)
+    dq, dk, dv = O.backward(run.dout, run.q, run.k, run.v, out, lse, run.q_offsets, run.kv_offsets,
+                            run.hist_len, run.n_targets, run.scale, layer, **rt)
+    if per_head:
+        dk, dv = sum_over_group(dk, case.cfg.Hkv), sum_over_group(dv, case.cfg.Hkv)
     return out, lse, dq, dk, dv
+
+
+def sum_over_group(per_head: np.ndarray, Hkv: int) -> np.ndarray:
+    """[rows, Hq, d] per-query-head gradients of repeated K/V -> [rows, Hkv, d]: summed over each kv head's query heads."""
+    rows, Hq, d = per_head.shape
+    return per_head.reshape(rows, Hkv, Hq // Hkv, d).sum(axis=2)
 
 
 def assert_close(name: str, got: np.ndarray, ref: np.ndarray, dtype: str) -> None:
@@ -88,7 +104,8 @@ def run_library(case: inputs.Case, with_bwd: bool) -> dict:
     return g
 
 
-def compare_with_oracle(case: inputs.Case, g: dict, with_bwd: bool, users=None, kv_group=None, compare=None) -> None:
+def compare_with_oracle(case: inputs.Case, g: dict, with_bwd: bool, users=None, kv_group=None, compare=None,
+                        per_head: bool = False) -> None:
     """Compare device results `g` of the whole case with the oracle run on all users (users=None) or on exactly the
     listed ones (users are independent samples) and, if kv_group is given, on that kv head and its query heads only."""
     dt = case.cfg.dtype
@@ -105,7 +122,7 @@ def compare_with_oracle(case: inputs.Case, g: dict, with_bwd: bool, users=None, 
         hs, gs = slice(kv_group * r, (kv_group + 1) * r), slice(kv_group, kv_group + 1)
         ref_case = inputs.take_kv_group(ref_case, kv_group)
     say(f"    oracle on {ref_case.batch} users, {ref_case.cfg.Hq} heads ...")
-    ref = oracle_all(ref_case, with_bwd)
+    ref = oracle_all(ref_case, with_bwd, per_head)
 
     def rows_of(t, rows, heads):   # [rows, heads, d] slice, taken on the device
         t = t if rows is None else t.index_select(0, rows)
