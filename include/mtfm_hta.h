@@ -104,6 +104,28 @@ MTFM_HTA_API int mtfm_hta_fwd(const void* q, const void* k, const void* v, void*
                  void* stream);
 
 /*
+ * mtfm_hta_fwd for callers that cannot allocate device memory or hand over a workspace: code running under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and kernels as mtfm_hta_fwd
+ * without `workspace` / `workspace_bytes`: what that call keeps in the caller's workspace (work counters, user
+ * schedule, the partial results of a forward pass that splits its keys) lives in a buffer of
+ * MTFM_HTA_STATIC_SCRATCH_BYTES built into the library, one copy in the memory of each GPU the library has run on,
+ * held until the process ends.  The call allocates and frees nothing, on the host or on the device.
+ * A call that needs more scratch memory than that (mtfm_hta_workspace_bytes(..., is_bwd = 0, ...) says how much; only
+ * a forward pass that splits its keys over many partial results can, e.g. several requests with hundreds of
+ * candidates at head_dim 128) returns MTFM_HTA_ERR_WORKSPACE and enqueues nothing; use mtfm_hta_fwd then.
+ * All calls on one GPU share that GPU's buffer: calls that may overlap in time (different streams, different threads)
+ * race and must be serialised by the caller, or use mtfm_hta_fwd with a workspace each.  Consecutive calls on one
+ * stream are safe.  The buffer's address is looked up on the first call on each device; make that first call
+ * outside a graph capture.
+ */
+#define MTFM_HTA_STATIC_SCRATCH_BYTES (8u << 20)
+MTFM_HTA_API int mtfm_hta_fwd_static(const void* q, const void* k, const void* v, void* out, float* lse,
+                 const int32_t* q_offsets, const int32_t* kv_offsets, const int32_t* hist_len,
+                 const int32_t* n_targets, int32_t batch, int64_t total_q, int64_t total_kv,
+                 int32_t max_hist, int32_t max_targets, int32_t Hq, int32_t Hkv, int32_t head_dim,
+                 float softmax_scale, int dtype, int layer, void* stream);
+
+/*
  * Backward of mtfm_hta_fwd for an upstream gradient dout: the probabilities are recomputed from the
  * saved logsumexp, p_ij = exp(scale*s_ij - lse_i), then with delta_i = <dout_i, out_i>,
  * ds_ij = p_ij (<dout_i, v_j> - delta_i):

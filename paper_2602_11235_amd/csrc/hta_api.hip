@@ -7,6 +7,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <mutex>
 
 namespace {
 
@@ -118,6 +119,45 @@ int check_scalars(int layer, int dtype, int32_t batch, int64_t total_q, int64_t 
 
 bool misaligned(const void* p) { return ((uintptr_t)p & 15u) != 0; }
 
+}  // namespace
+
+// ---------------------------------------------------------------------------------------------------------------
+// mtfm_hta_fwd_static: the forward call for callers that cannot allocate.  What mtfm_hta_fwd keeps in the caller's
+// workspace lives in `scratch`, a fixed array in device memory that every GPU the library runs on holds until the
+// process ends.  In host code the name `scratch` is only a handle for the runtime, not a device address: the address
+// of the array on the current device comes from hipGetSymbolAddress, once per device, and that pointer is what the
+// kernels get.
+static __device__ __align__(256) unsigned char scratch[MTFM_HTA_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[MAX_DEVICES] = {};  // device address of `scratch` on each device, resolved on first use
+
+// address of `scratch` on the current device, or null with the error recorded
+void* scratch_of_current_device() {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) {
+        fail(MTFM_HTA_ERR_LAUNCH, "hipGetDevice failed: %s", hipGetErrorString(e));
+        return nullptr;
+    }
+    if (dev < 0 || dev >= MAX_DEVICES) {
+        fail(MTFM_HTA_ERR_UNSUPPORTED, "device index %d outside 0..%d", dev, MAX_DEVICES - 1);
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) {
+            fail(MTFM_HTA_ERR_LAUNCH, "hipGetSymbolAddress(scratch) failed on device %d: %s", dev, hipGetErrorString(e));
+            return nullptr;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
 }  // namespace
 
 extern "C" {
@@ -255,6 +295,30 @@ int mtfm_hta_fwd(const void* q, const void* k, const void* v, void* out, float* 
     return fwd_impl(q, k, v, out, lse, q_offsets, kv_offsets, hist_len, nullptr, n_targets, nullptr, batch, total_q,
                     total_kv, max_hist, 0, max_targets, Hq, Hkv, head_dim, softmax_scale, dtype, layer, workspace,
                     workspace_bytes, stream);
+}
+
+int mtfm_hta_fwd_static(const void* q, const void* k, const void* v, void* out, float* lse, const int32_t* q_offsets,
+                        const int32_t* kv_offsets, const int32_t* hist_len, const int32_t* n_targets, int32_t batch,
+                        int64_t total_q, int64_t total_kv, int32_t max_hist, int32_t max_targets, int32_t Hq,
+                        int32_t Hkv, int32_t head_dim, float softmax_scale, int dtype, int layer, void* stream) {
+    int rc = check_scalars(layer, dtype, batch, total_q, total_kv, max_hist, 0, max_targets, Hq, Hkv, head_dim);
+    if (rc != MTFM_HTA_OK) return rc;
+    const int splits = forward_splits(dtype, layer, batch, max_hist, 0, max_targets, Hq, Hkv, head_dim);
+    const size_t need = plan_workspace(dtype, 0, batch, total_q, Hq, false, splits, head_dim).total;
+    if (need > (size_t)MTFM_HTA_STATIC_SCRATCH_BYTES)
+        return fail(MTFM_HTA_ERR_WORKSPACE,
+                    "mtfm_hta_fwd_static: this call needs %zu bytes of scratch memory, the built-in buffer holds %zu; "
+                    "use mtfm_hta_fwd with a workspace of the caller's", need, (size_t)MTFM_HTA_STATIC_SCRATCH_BYTES);
+    void* ws = nullptr;
+    if (need > 0 && batch > 0 && total_q > 0) {
+        ws = scratch_of_current_device();
+        if (!ws) return MTFM_HTA_ERR_LAUNCH;
+    }
+    // Everything the kernels expect to find zeroed in the scratch memory (the work counters) is cleared by the
+    // schedule kernel at the start of the call; the rest is written before it is read.
+    return fwd_impl(q, k, v, out, lse, q_offsets, kv_offsets, hist_len, nullptr, n_targets, nullptr, batch, total_q,
+                    total_kv, max_hist, 0, max_targets, Hq, Hkv, head_dim, softmax_scale, dtype, layer, ws,
+                    ws ? (size_t)MTFM_HTA_STATIC_SCRATCH_BYTES : 0, stream);
 }
 
 int mtfm_hta_fwd_rt(const void* q, const void* k, const void* v, void* out, float* lse, const int32_t* q_offsets,

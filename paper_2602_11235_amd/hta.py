@@ -17,7 +17,7 @@ LAYER_FULL, LAYER_TARGET = 0, 1
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_LAUNCH = 0, -1, -2, -3, -4
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmtfm_hta.so")
-EXPORTS = ("mtfm_hta_workspace_bytes", "mtfm_hta_fwd", "mtfm_hta_bwd", "mtfm_hta_validate_host",
+EXPORTS = ("mtfm_hta_workspace_bytes", "mtfm_hta_fwd", "mtfm_hta_fwd_static", "mtfm_hta_bwd", "mtfm_hta_validate_host",
            "mtfm_hta_workspace_bytes_rt", "mtfm_hta_fwd_rt", "mtfm_hta_bwd_rt", "mtfm_hta_validate_host_rt",
            "mtfm_hta_last_error", "mtfm_hta_version", "mtfm_hta_timing_enable", "mtfm_hta_timing_read")
 KERNEL_FWD, KERNEL_BWD_SELF, KERNEL_BWD_DQ, KERNEL_BWD_DKDV = 0, 1, 2, 3
@@ -47,6 +47,8 @@ def load_library() -> ctypes.CDLL:
     tail = [i32, i64, i64, i32, i32, i32, i32, i32, f32, ci, ci, vp, sz, vp]
     lib.mtfm_hta_fwd.restype = ci
     lib.mtfm_hta_fwd.argtypes = [vp] * 9 + tail
+    lib.mtfm_hta_fwd_static.restype = ci
+    lib.mtfm_hta_fwd_static.argtypes = [vp] * 9 + tail[:-3] + [vp]
     lib.mtfm_hta_bwd.restype = ci
     lib.mtfm_hta_bwd.argtypes = [vp] * 13 + tail
     lib.mtfm_hta_validate_host.restype = ci
@@ -140,6 +142,18 @@ def mtfm_hta_fwd(q, k, v, out, lse, q_offsets, kv_offsets, hist_len, n_targets, 
                                        _ptr(kv_offsets), _ptr(hist_len), _ptr(n_targets), batch, total_q,
                                        total_kv, max_hist, max_targets, Hq, Hkv, head_dim, softmax_scale, dtype,
                                        layer, _ptr(workspace), workspace_bytes, _stream_handle(stream)))
+
+
+STATIC_SCRATCH_BYTES = 8 << 20
+
+
+def mtfm_hta_fwd_static(q, k, v, out, lse, q_offsets, kv_offsets, hist_len, n_targets, batch, total_q, total_kv,
+                        max_hist, max_targets, Hq, Hkv, head_dim, softmax_scale, dtype, layer, stream=None) -> None:
+    """The forward pass without a workspace argument: scratch memory built into the library, nothing allocated."""
+    _check(load_library().mtfm_hta_fwd_static(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), _ptr(q_offsets),
+                                              _ptr(kv_offsets), _ptr(hist_len), _ptr(n_targets), batch, total_q,
+                                              total_kv, max_hist, max_targets, Hq, Hkv, head_dim, softmax_scale,
+                                              dtype, layer, _stream_handle(stream)))
 
 
 def mtfm_hta_bwd(dout, q, k, v, out, lse, dq, dk, dv, q_offsets, kv_offsets, hist_len, n_targets, batch, total_q,

@@ -21,7 +21,7 @@ def _declared_symbols():
 def test_library_exports_every_declared_symbol():
     lib = hta.load_library()
     names = _declared_symbols()
-    assert set(names) == set(hta.EXPORTS) and len(names) == 12
+    assert set(names) == set(hta.EXPORTS) and len(names) == 13
     for n in names:
         assert getattr(lib, n) is not None
     assert re.fullmatch(r"\d+\.\d+\.\d+", hta.mtfm_hta_version())

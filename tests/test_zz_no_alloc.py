@@ -1,0 +1,85 @@
+"""mtfm_hta_fwd_static: the forward call that takes no workspace and allocates nothing (its scratch memory is a fixed
+array inside the library).  Called through the C ABI and compared with mtfm_hta_fwd on the same inputs -- same kernels,
+so bit for bit, which is well inside the parity tolerance -- on two calls in a row, the second on a smaller input (the
+scratch memory still holds the first call's contents then), and against the float64 oracle."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2602_11235_amd import hta, inputs
+from tests.hta_testlib import assert_close, device_batch, host, oracle_all
+
+FULL, TARGET = inputs.LAYER_FULL, inputs.LAYER_TARGET
+
+
+def both_ways(case):
+    """(out, lse) of mtfm_hta_fwd with a caller-owned workspace and of mtfm_hta_fwd_static, results pre-filled with NaN."""
+    b = device_batch(case)
+    ref_out, ref_lse = (t.clone() for t in b.forward())
+    torch.cuda.synchronize()
+    out = torch.full_like(b.q, float("nan"))
+    lse = torch.full_like(b.lse, float("nan"))
+    torch.cuda.synchronize()
+    before = torch.cuda.memory_stats()["allocation.all.allocated"]
+    hta.mtfm_hta_fwd_static(b.q, b.k, b.v, out, lse, b.q_offsets, b.kv_offsets, b.hist_len, b.n_targets, b.batch,
+                            b.total_q, b.total_kv, b.max_hist, b.max_targets, b.Hq, b.Hkv, b.head_dim, b.softmax_scale,
+                            b.dtype, b.layer)
+    torch.cuda.synchronize()
+    assert torch.cuda.memory_stats()["allocation.all.allocated"] == before   # (torch's allocator was not involved either)
+    return (ref_out, ref_lse), (out, lse)
+
+
+def check(case):
+    (ref_out, ref_lse), (out, lse) = both_ways(case)
+    assert torch.equal(out, ref_out) and torch.equal(lse, ref_lse)
+    r_out, r_lse = oracle_all(case, with_bwd=False)
+    assert_close("out", host(out), r_out, case.cfg.dtype)
+    assert_close("lse", host(lse), r_lse, case.cfg.dtype)
+
+
+@pytest.mark.gpu
+def test_two_calls_in_a_row_the_second_on_a_smaller_input():
+    big = inputs.make_case(inputs.custom_config("static_big", FULL, [700, 64, 0, 300, 129, 1000] * 12,
+                                                [33, 5, 2, 64, 0, 17] * 12, 8, 2, 64, seed=61), with_dout=False)
+    small = inputs.make_case(inputs.custom_config("static_small", FULL, [130, 0, 65], [7, 3, 40], 8, 2, 64, seed=62),
+                             with_dout=False)
+    check(big)
+    check(small)
+    check(big)
+
+
+@pytest.mark.gpu
+def test_split_forward_and_other_shapes():
+    # a few requests: the keys are split and the partial results live in the built-in scratch memory; then the same
+    # call on one request with fewer, shorter splits; then the fp32 path (no scratch memory at all) and d = 128
+    many = inputs.make_case(inputs.custom_config("static_split", TARGET, [2048, 0, 1, 63, 128, 65, 1000, 64],
+                                                 [16, 5, 1, 33, 64, 2, 70, 0], 8, 2, 64, seed=63), with_dout=False)
+    one = inputs.make_case(inputs.custom_config("static_split_one", TARGET, [600], [16], 8, 2, 64, seed=64),
+                           with_dout=False)
+    assert device_batch(many).fwd_workspace_bytes > 65536
+    check(many)
+    check(one)
+    check(inputs.make_case(inputs.custom_config("static_fp32", FULL, [40, 0, 64], [8, 3, 0], 4, 1, 16, dtype="fp32",
+                                                std=0.5, seed=65), with_dout=False))
+    check(inputs.make_case(inputs.custom_config("static_d128", FULL, [257, 31], [129, 0], 16, 2, 128, seed=66),
+                           with_dout=False))
+
+
+def test_sizes_beyond_the_built_in_scratch_memory_are_refused_on_the_host():
+    """Four requests of 8192 history tokens at head_dim 128 split their keys into more partial results than the
+    built-in buffer holds: refused with a clear message before anything touches a device (runs without a GPU)."""
+    lib = hta.load_library()
+    need = hta.mtfm_hta_workspace_bytes(TARGET, hta.BF16, False, 4, 256, 4 * 8256, 8192, 64, 16, 2, 128)
+    assert need > hta.STATIC_SCRATCH_BYTES
+    rc = lib.mtfm_hta_fwd_static(*([4096] * 9), 4, 256, 4 * 8256, 8192, 64, 16, 2, 128, ctypes.c_float(0.1), hta.BF16,
+                                 TARGET, None)
+    assert rc == hta.ERR_WORKSPACE
+    msg = hta.mtfm_hta_last_error()
+    assert str(need) in msg and str(hta.STATIC_SCRATCH_BYTES) in msg and "mtfm_hta_fwd" in msg
+    # bad scalars are refused as by mtfm_hta_fwd, and an empty batch is a successful no-op
+    assert lib.mtfm_hta_fwd_static(*([4096] * 9), 2, 10, 10, 4, 1, 8, 3, 64, ctypes.c_float(0.1), hta.BF16, FULL,
+                                   None) == hta.ERR_INVALID_ARG
+    assert lib.mtfm_hta_fwd_static(*([None] * 9), 0, 0, 0, 0, 0, 8, 2, 64, ctypes.c_float(0.1), hta.BF16, FULL,
+                                   None) == hta.OK
