@@ -88,11 +88,13 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb,
         lim[rb] = RT ? p.lim[q_base + row] : L;
     }
 
-    float m[RB], l[RB];
+    float m[RB], l[RB], grow_at[RB];
+    const float inv_c2 = 1.f / c2;
     floatx16 O[RB][NDB];
 #pragma unroll
     for (int rb = 0; rb < RB; rb++) {
         m[rb] = -INFINITY;
+        grow_at[rb] = -INFINITY;
         l[rb] = 0.f;
 #pragma unroll
         for (int db = 0; db < NDB; db++)
@@ -170,13 +172,17 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb,
             float mx = S[rb][0];
 #pragma unroll
             for (int v = 1; v < 16; v++) mx = fmaxf(mx, S[rb][v]);
-            mx = fmaxf(mx, other_half(mx)) * c2;
-            const bool grow = mx > m[rb] + RESCALE_SLACK;
-            if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+            // The two lanes of a row (32 apart) each hold half of its keys: as long as neither half outgrows the
+            // row's reference by more than the slack -- tested on the raw dot products against grow_at[rb] =
+            // (m + slack) / c2 -- they need not even exchange their maxima.
+            if (__builtin_amdgcn_ballot_w64(mx > grow_at[rb]) != 0) {
+                mx = fmaxf(mx, other_half(mx)) * c2;
+                const bool grow = mx > m[rb] + RESCALE_SLACK;
                 const float m_new = grow ? mx : m[rb];
                 // 1 for the rows that keep their reference (which may still be -inf when rows see different keys)
                 const float alpha = grow ? fast_exp2(m[rb] - m_new) : 1.f;
                 m[rb] = m_new;
+                grow_at[rb] = (m_new + RESCALE_SLACK) * inv_c2;
                 l[rb] *= alpha;
 #pragma unroll
                 for (int db = 0; db < NDB; db++)
