@@ -57,7 +57,8 @@ typedef enum {
 } mtfm_hta_status;
 
 /* element type of q, k, v, out, dout, dq, dk, dv */
-enum { MTFM_HTA_BF16 = 0, /* bfloat16 storage, MFMA with fp32 accumulation; head_dim in {32, 64, 128} */
+enum { MTFM_HTA_BF16 = 0, /* bfloat16 storage, MFMA with fp32 accumulation; head_dim in {32, 64, 128} (a 16-wide head
+                             fills half of the 32-wide matrix tiles: such shapes go through MTFM_HTA_FP32) */
        MTFM_HTA_FP32 = 1  /* float32 storage and arithmetic (plain FMA debug path); 1 <= head_dim <= 128 */ };
 
 /* which layer of a block: queries = all tokens, or target tokens only */

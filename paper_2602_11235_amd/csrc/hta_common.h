@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace hta {
 
 // Everything one call needs, passed to the kernels by value.
@@ -51,11 +53,11 @@ struct Params {
 };
 
 // number of query rows a user can have at most, from the host-known bounds
-inline int64_t max_query_rows(const Params& p) {
+__host__ __device__ inline int64_t max_query_rows(const Params& p) {
     return p.layer == 0 ? (int64_t)p.max_hist + p.max_rt + p.max_targets : (int64_t)p.max_targets;
 }
 // number of keys a user's tile loops can reach at most: history, then real-time tokens
-inline int64_t max_lead_keys(const Params& p) { return (int64_t)p.max_hist + p.max_rt; }
+__host__ __device__ inline int64_t max_lead_keys(const Params& p) { return (int64_t)p.max_hist + p.max_rt; }
 // per-row limits of mask rule 2 (a launch of its own at the start of a call with real-time tokens)
 hipError_t launch_rt_limits(const Params& p, hipStream_t s);
 
@@ -127,15 +129,20 @@ __device__ inline int queue_resolve(int32_t* counters, int xcd, unsigned taken, 
 // workgroups of `Kernel` (at `threads` threads, no dynamic LDS) that the current device holds at once
 template <auto Kernel>
 inline int resident_workgroups(int threads) {
-    static int cached = 0;
-    if (cached == 0) {
-        int dev = 0, n_cu = 0, per_cu = 0;
-        if (hipGetDevice(&dev) != hipSuccess) return 256;
-        if (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 256;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, Kernel, threads, 0) != hipSuccess) return 256;
-        cached = n_cu * (per_cu > 0 ? per_cu : 1);
+    constexpr int MAX_DEVICES = 64;
+    static std::atomic<int> cached[MAX_DEVICES];  // per device (0: not asked yet); the answer never changes
+    int dev = 0, n_cu = 0, per_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 256;
+    const bool cacheable = dev >= 0 && dev < MAX_DEVICES;
+    if (cacheable) {
+        const int known = cached[dev].load(std::memory_order_relaxed);
+        if (known > 0) return known;
     }
-    return cached;
+    if (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 256;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, Kernel, threads, 0) != hipSuccess) return 256;
+    const int n = n_cu * (per_cu > 0 ? per_cu : 1);
+    if (cacheable) cached[dev].store(n, std::memory_order_relaxed);
+    return n;
 }
 // fill `n` 32-bit words with zero (a kernel, so that a caller may capture the call in a HIP graph)
 hipError_t launch_zero_words(void* ptr, size_t n_words, hipStream_t s);

@@ -1,7 +1,8 @@
 // Work schedule of a jagged batch, built on the device from hist_len / n_targets (no host round trip).
 //
 // Under the hybrid mask (rules 1 and 3, Section 3.2.2) user b owns exactly the tiles
-// (query rows) x (history keys): rows = L_b + T_b in a full layer, T_b in a target layer, keys = L_b;
+// (query rows) x (history keys): rows = L_b + T_b in a full layer, T_b in a target layer, keys = L_b
+// (with real-time tokens, rule 2, their keys and rows count like history ones);
 // nothing else is ever issued (the self key of a target row is a per-row term).  The attention
 // kernels enumerate those tiles from (L_b, T_b) themselves; what the schedule adds is the ORDER of
 // the users: workgroups are dispatched user-major, so listing users by decreasing tile count
@@ -15,8 +16,9 @@ constexpr int SCHED_THREADS = 1024;
 constexpr int RANK_SORT_MAX = 4096;   // exact, deterministic rank sort up to this many users
 constexpr int N_BUCKETS = 2048;       // bucketed counting sort above it
 
+// tiles a user owns: (query rows) x (keys that run through the tile loops: history, then real-time tokens)
 __device__ inline float user_cost(const Params& p, int b) {
-    const float L = (float)p.hist_len[b], T = (float)p.n_targets[b];
+    const float L = (float)p.hist_len[b] + (p.rt_len ? (float)p.rt_len[b] : 0.f), T = (float)p.n_targets[b];
     return (p.layer == 0 ? L + T : T) * L;
 }
 
@@ -45,8 +47,9 @@ __global__ __launch_bounds__(SCHED_THREADS) void schedule_bucket_kernel(Params p
     __shared__ int start[N_BUCKETS];
     const int B = p.batch;
     if (threadIdx.x < QUEUE_WORDS) counters[threadIdx.x] = 0;
-    const float rows_max = (float)(p.layer == 0 ? (int64_t)p.max_hist + p.max_targets : (int64_t)p.max_targets);
-    const float inv = (float)(N_BUCKETS - 1) / fmaxf(rows_max * (float)p.max_hist, 1.f);
+    const float keys_max = (float)max_lead_keys(p);
+    const float rows_max = p.layer == 0 ? keys_max + (float)p.max_targets : (float)p.max_targets;
+    const float inv = (float)(N_BUCKETS - 1) / fmaxf(rows_max * keys_max, 1.f);
     for (int i = threadIdx.x; i < N_BUCKETS; i += SCHED_THREADS) count[i] = 0;
     __syncthreads();
     for (int b = threadIdx.x; b < B; b += SCHED_THREADS) {
