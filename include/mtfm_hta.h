@@ -57,8 +57,10 @@ typedef enum {
 } mtfm_hta_status;
 
 /* element type of q, k, v, out, dout, dq, dk, dv */
-enum { MTFM_HTA_BF16 = 0, /* bfloat16 storage, MFMA with fp32 accumulation; head_dim in {32, 64, 128} (a 16-wide head
-                             fills half of the 32-wide matrix tiles: such shapes go through MTFM_HTA_FP32) */
+enum { MTFM_HTA_BF16 = 0, /* bfloat16 storage, MFMA with fp32 accumulation; head_dim in {16, 32, 64, 128}.  A 16-wide
+                             head fills half of the 32-wide matrix tiles: the library runs it at 32 on copies of the
+                             tensors padded with zero features, kept in the workspace (which grows by those copies);
+                             results are those of the 16-wide problem, the cost is that of head_dim 32 plus the copies */
        MTFM_HTA_FP32 = 1  /* float32 storage and arithmetic (plain FMA debug path); 1 <= head_dim <= 128 */ };
 
 /* which layer of a block: queries = all tokens, or target tokens only */

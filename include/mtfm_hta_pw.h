@@ -12,7 +12,7 @@
  * pass needs neither the forward output nor anything saved by the forward pass.  Backward, with x_ij = scale <q_i, k_j>:
  *   dv_j = norm sum_i silu(x_ij) dout_i        dx_ij = norm <dout_i, v_j> silu'(x_ij),  silu'(x) = s (1 + x (1 - s)), s = sigmoid(x)
  *   dq_i = scale sum_j dx_ij k_j               dk_j = scale sum_i dx_ij q_i             (sums over the query heads of a kv head)
- * bf16 with head_dim in {32, 64, 128} on the MFMA kernels, fp32 on the debug path, as in mtfm_hta.h.  The functions
+ * bf16 with head_dim in {16, 32, 64, 128} on the MFMA kernels, fp32 on the debug path, as in mtfm_hta.h.  The functions
  * with the _rt suffix take samples with real-time tokens (mask rule 2), with the arguments and the readings of the
  * _rt functions of mtfm_hta.h.  A forward call on a few users splits the keys over workgroups as mtfm_hta_fwd does
  * (the partial results are partial sums here); the workspace functions account for it.

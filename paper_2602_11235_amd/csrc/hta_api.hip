@@ -35,13 +35,17 @@ int report_error(int code, const char* fmt, ...) {
 
 namespace {
 
+// head_dim the bf16 kernels run at: 16-wide heads are zero-padded to the 32-wide matrix tiles (copies in the workspace)
+inline bool padded_head(int dtype, int32_t d) { return dtype == MTFM_HTA_BF16 && d == hta::BF16_PADDED_FROM; }
+inline int32_t kernel_head_dim(int dtype, int32_t d) { return padded_head(dtype, d) ? hta::BF16_PADDED_TO : d; }
+
 // key splits of a forward call, from its host-known bounds (1: none)
 int forward_splits(int dtype, int layer, int32_t batch, int32_t max_hist, int32_t max_rt, int32_t max_targets, int32_t Hq,
                    int32_t Hkv, int32_t d) {
     if (dtype != MTFM_HTA_BF16) return 1;
     const int64_t keys = (int64_t)max_hist + max_rt;
     const int64_t rows = layer == MTFM_HTA_LAYER_FULL ? keys + max_targets : (int64_t)max_targets;
-    return hta::fwd_key_splits(batch, Hq, Hkv, d, rows, keys);
+    return hta::fwd_key_splits(batch, Hq, Hkv, kernel_head_dim(dtype, d), rows, keys);
 }
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -49,6 +53,7 @@ inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 struct Workspace {
     size_t order_off, delta_off, lse_off, lim_off, opart_off, lsepart_off, total;
     int splits;
+    size_t pad_off, pad_q, pad_kv;  // head_dim 16: where the zero-padded copies start, bytes of one q-shaped / kv-shaped copy
 };
 
 // Layout of the caller's workspace (bf16 path; the fp32 debug path needs none):
@@ -57,9 +62,13 @@ struct Workspace {
 //   with real-time tokens (both dtypes): lim [total_q] int32, the per-row limits of mask rule 2, rebuilt by every call
 //   forward pass split over the keys (`splits` > 1: few requests, decided from the host-known bounds alone):
 //   partial outputs [splits][total_q][Hq][d] f32 and their logsumexps [splits][Hq][total_q] f32
+//   bf16 head_dim 16: copies of the tensors zero-padded to 32 features, which is what the kernels then see --
+//   q, k, v, out (forward); dout, q, k, v, out, dq, dk, dv (backward)
 Workspace plan_workspace(int dtype, int is_bwd, int32_t batch, int64_t total_q, int32_t Hq, bool has_rt, int splits = 1,
-                         int32_t d = 0) {
-    Workspace w{0, 0, 0, 0, 0, 0, 0, 1};
+                         int32_t d = 0, int64_t total_kv = 0, int32_t Hkv = 0) {
+    Workspace w{0, 0, 0, 0, 0, 0, 0, 1, 0, 0, 0};
+    const bool padded = padded_head(dtype, d);
+    d = kernel_head_dim(dtype, d);
     if (has_rt) {
         w.lim_off = 0;
         w.total = align256((size_t)total_q * sizeof(int32_t));
@@ -78,6 +87,12 @@ Workspace plan_workspace(int dtype, int is_bwd, int32_t batch, int64_t total_q, 
         w.total += align256((size_t)splits * total_q * Hq * d * sizeof(float));
         w.lsepart_off = w.total;
         w.total += align256((size_t)splits * total_q * Hq * sizeof(float));
+    }
+    if (padded) {
+        w.pad_off = w.total;
+        w.pad_q = align256((size_t)total_q * Hq * hta::BF16_PADDED_TO * 2);
+        w.pad_kv = align256((size_t)total_kv * Hkv * hta::BF16_PADDED_TO * 2);
+        w.total += is_bwd ? 4 * w.pad_q + 4 * w.pad_kv : 2 * w.pad_q + 2 * w.pad_kv;
     }
     return w;
 }
@@ -109,8 +124,8 @@ int check_scalars(int layer, int dtype, int32_t batch, int64_t total_q, int64_t 
     if (d <= 0) return fail(MTFM_HTA_ERR_INVALID_ARG, "head_dim must be positive, got %d", d);
     if (dtype == MTFM_HTA_FP32) {
         if (d > 128) return fail(MTFM_HTA_ERR_UNSUPPORTED, "fp32 path supports head_dim <= 128, got %d", d);
-    } else if (!hta::bf16_supported(d, Hq, Hkv)) {
-        return fail(MTFM_HTA_ERR_UNSUPPORTED, "bf16 path supports head_dim in {32, 64, 128}, got %d", d);
+    } else if (!hta::bf16_supported(kernel_head_dim(dtype, d), Hq, Hkv)) {
+        return fail(MTFM_HTA_ERR_UNSUPPORTED, "bf16 path supports head_dim in {16, 32, 64, 128}, got %d", d);
     }
     if ((int64_t)max_hist + max_rt + max_targets >= (1ll << 31))
         return fail(MTFM_HTA_ERR_INVALID_ARG, "max_hist + max_rt + max_targets overflows int32");
@@ -171,7 +186,7 @@ size_t mtfm_hta_workspace_bytes(int layer, int dtype, int is_bwd, int32_t batch,
     if (check_scalars(layer, dtype, batch, total_q, total_kv, max_hist, 0, max_targets, Hq, Hkv, head_dim) != MTFM_HTA_OK)
         return (size_t)-1;
     const int splits = is_bwd ? 1 : forward_splits(dtype, layer, batch, max_hist, 0, max_targets, Hq, Hkv, head_dim);
-    return plan_workspace(dtype, is_bwd, batch, total_q, Hq, false, splits, head_dim).total;
+    return plan_workspace(dtype, is_bwd, batch, total_q, Hq, false, splits, head_dim, total_kv, Hkv).total;
 }
 
 size_t mtfm_hta_workspace_bytes_rt(int layer, int dtype, int is_bwd, int32_t batch, int64_t total_q, int64_t total_kv,
@@ -180,7 +195,7 @@ size_t mtfm_hta_workspace_bytes_rt(int layer, int dtype, int is_bwd, int32_t bat
     if (check_scalars(layer, dtype, batch, total_q, total_kv, max_hist, max_rt, max_targets, Hq, Hkv, head_dim) != MTFM_HTA_OK)
         return (size_t)-1;
     const int splits = is_bwd ? 1 : forward_splits(dtype, layer, batch, max_hist, max_rt, max_targets, Hq, Hkv, head_dim);
-    return plan_workspace(dtype, is_bwd, batch, total_q, Hq, true, splits, head_dim).total;
+    return plan_workspace(dtype, is_bwd, batch, total_q, Hq, true, splits, head_dim, total_kv, Hkv).total;
 }
 
 static int validate_host_impl(const int32_t* q_offsets, const int32_t* kv_offsets, const int32_t* hist_len,
@@ -252,9 +267,22 @@ static int fwd_impl(const void* q, const void* k, const void* v, void* out, floa
         return fail(MTFM_HTA_ERR_INVALID_ARG, "q, k, v, out must be 16-byte aligned");
     if (has_rt && !timestamps) return fail(MTFM_HTA_ERR_INVALID_ARG, "null pointer argument");
     const int splits = forward_splits(dtype, layer, batch, max_hist, max_rt, max_targets, Hq, Hkv, head_dim);
-    const Workspace w = plan_workspace(dtype, 0, batch, total_q, Hq, has_rt, splits, head_dim);
+    const Workspace w = plan_workspace(dtype, 0, batch, total_q, Hq, has_rt, splits, head_dim, total_kv, Hkv);
     rc = check_workspace(w, workspace, workspace_bytes);
     if (rc != MTFM_HTA_OK) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    hipError_t e = hipSuccess;
+    void* const caller_out = out;
+    const bool padded = padded_head(dtype, head_dim);
+    if (padded) {  // the kernels see copies zero-padded to 32 features; the result is narrowed again at the end
+        char* pad = (char*)workspace + w.pad_off;
+        void* q32 = pad; void* out32 = pad + w.pad_q; void* k32 = pad + 2 * w.pad_q; void* v32 = pad + 2 * w.pad_q + w.pad_kv;
+        e = hta::launch_widen16(q, q32, total_q * Hq, s);
+        if (e == hipSuccess) e = hta::launch_widen16(k, k32, total_kv * Hkv, s);
+        if (e == hipSuccess) e = hta::launch_widen16(v, v32, total_kv * Hkv, s);
+        if (e != hipSuccess) return fail(MTFM_HTA_ERR_LAUNCH, "forward launch failed: %s", hipGetErrorString(e));
+        q = q32; k = k32; v = v32; out = out32; head_dim = hta::BF16_PADDED_TO;
+    }
     hta::Params p{};
     p.q = q; p.k = k; p.v = v; p.out = out; p.lse = lse;
     p.q_off = q_offsets; p.kv_off = kv_offsets; p.hist_len = hist_len; p.n_targets = n_targets;
@@ -262,8 +290,6 @@ static int fwd_impl(const void* q, const void* k, const void* v, void* out, floa
     p.Hq = Hq; p.Hkv = Hkv; p.d = head_dim; p.scale = softmax_scale; p.layer = layer;
     p.rt_len = rt_len; p.ts = timestamps; p.max_rt = max_rt;
     p.pointwise = pointwise ? 1 : 0; p.norm = norm;
-    hipStream_t s = (hipStream_t)stream;
-    hipError_t e = hipSuccess;
     if (has_rt) {
         p.lim = (int32_t*)((char*)workspace + w.lim_off);
         e = hta::launch_rt_limits(p, s);
@@ -283,6 +309,7 @@ static int fwd_impl(const void* q, const void* k, const void* v, void* out, floa
         }
     }
     if (e == hipSuccess) e = dtype == MTFM_HTA_FP32 ? hta::launch_fwd_fp32(p, s) : hta::launch_fwd_bf16(p, s);
+    if (e == hipSuccess && padded) e = hta::launch_narrow16(out, caller_out, total_q * Hq, s);
     if (e != hipSuccess) return fail(MTFM_HTA_ERR_LAUNCH, "forward launch failed: %s", hipGetErrorString(e));
     return MTFM_HTA_OK;
 }
@@ -304,7 +331,7 @@ int mtfm_hta_fwd_static(const void* q, const void* k, const void* v, void* out, 
     int rc = check_scalars(layer, dtype, batch, total_q, total_kv, max_hist, 0, max_targets, Hq, Hkv, head_dim);
     if (rc != MTFM_HTA_OK) return rc;
     const int splits = forward_splits(dtype, layer, batch, max_hist, 0, max_targets, Hq, Hkv, head_dim);
-    const size_t need = plan_workspace(dtype, 0, batch, total_q, Hq, false, splits, head_dim).total;
+    const size_t need = plan_workspace(dtype, 0, batch, total_q, Hq, false, splits, head_dim, total_kv, Hkv).total;
     if (need > (size_t)MTFM_HTA_STATIC_SCRATCH_BYTES)
         return fail(MTFM_HTA_ERR_WORKSPACE,
                     "mtfm_hta_fwd_static: this call needs %zu bytes of scratch memory, the built-in buffer holds %zu; "
@@ -354,9 +381,27 @@ static int bwd_impl(const void* dout, const void* q, const void* k, const void* 
         misaligned(dk) || misaligned(dv))
         return fail(MTFM_HTA_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
     if (has_rt && !timestamps) return fail(MTFM_HTA_ERR_INVALID_ARG, "null pointer argument");
-    const Workspace w = plan_workspace(dtype, 1, batch, total_q, Hq, has_rt);
+    const Workspace w = plan_workspace(dtype, 1, batch, total_q, Hq, has_rt, 1, head_dim, total_kv, Hkv);
     rc = check_workspace(w, workspace, workspace_bytes);
     if (rc != MTFM_HTA_OK) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    hipError_t e = hipSuccess;
+    void* const caller_dq = dq; void* const caller_dk = dk; void* const caller_dv = dv;
+    const bool padded = padded_head(dtype, head_dim);
+    if (padded) {  // as in the forward call: the kernels see zero-padded copies, the gradients are narrowed at the end
+        char* pad = (char*)workspace + w.pad_off;
+        void* dout32 = pad; void* q32 = pad + w.pad_q; void* out32 = pad + 2 * w.pad_q; void* dq32 = pad + 3 * w.pad_q;
+        char* kv = pad + 4 * w.pad_q;
+        void* k32 = kv; void* v32 = kv + w.pad_kv; void* dk32 = kv + 2 * w.pad_kv; void* dv32 = kv + 3 * w.pad_kv;
+        e = hta::launch_widen16(dout, dout32, total_q * Hq, s);
+        if (e == hipSuccess) e = hta::launch_widen16(q, q32, total_q * Hq, s);
+        if (e == hipSuccess && out) e = hta::launch_widen16(out, out32, total_q * Hq, s);
+        if (e == hipSuccess) e = hta::launch_widen16(k, k32, total_kv * Hkv, s);
+        if (e == hipSuccess) e = hta::launch_widen16(v, v32, total_kv * Hkv, s);
+        if (e != hipSuccess) return fail(MTFM_HTA_ERR_LAUNCH, "backward launch failed: %s", hipGetErrorString(e));
+        dout = dout32; q = q32; k = k32; v = v32; if (out) out = out32;
+        dq = dq32; dk = dk32; dv = dv32; head_dim = hta::BF16_PADDED_TO;
+    }
     hta::Params p{};
     p.dout = dout; p.q = q; p.k = k; p.v = v; p.out = const_cast<void*>(out); p.lse = const_cast<float*>(lse);
     p.dq = dq; p.dk = dk; p.dv = dv;
@@ -370,8 +415,6 @@ static int bwd_impl(const void* dout, const void* q, const void* k, const void* 
         p.neg_delta = (float*)(base + w.delta_off);
         p.neg_lse_s = (float*)(base + w.lse_off);
     }
-    hipStream_t s = (hipStream_t)stream;
-    hipError_t e = hipSuccess;
     if (has_rt) {
         p.lim = (int32_t*)((char*)workspace + w.lim_off);
         e = hta::launch_rt_limits(p, s);
@@ -383,6 +426,11 @@ static int bwd_impl(const void* dout, const void* q, const void* k, const void* 
         p.queue = hta::schedule_queue(region, 0);  // the launchers add the kernel kind
     }
     if (e == hipSuccess) e = dtype == MTFM_HTA_FP32 ? hta::launch_bwd_fp32(p, s) : hta::launch_bwd_bf16(p, s);
+    if (e == hipSuccess && padded) {
+        e = hta::launch_narrow16(dq, caller_dq, total_q * Hq, s);
+        if (e == hipSuccess) e = hta::launch_narrow16(dk, caller_dk, total_kv * Hkv, s);
+        if (e == hipSuccess) e = hta::launch_narrow16(dv, caller_dv, total_kv * Hkv, s);
+    }
     if (e != hipSuccess) return fail(MTFM_HTA_ERR_LAUNCH, "backward launch failed: %s", hipGetErrorString(e));
     return MTFM_HTA_OK;
 }
@@ -414,7 +462,7 @@ size_t mtfm_hta_pw_workspace_bytes(int layer, int dtype, int is_bwd, int32_t bat
     if (check_scalars(layer, dtype, batch, total_q, total_kv, max_hist, 0, max_targets, Hq, Hkv, head_dim) != MTFM_HTA_OK)
         return (size_t)-1;
     const int splits = is_bwd ? 1 : forward_splits(dtype, layer, batch, max_hist, 0, max_targets, Hq, Hkv, head_dim);
-    return plan_workspace(dtype, is_bwd, batch, total_q, Hq, false, splits, head_dim).total;
+    return plan_workspace(dtype, is_bwd, batch, total_q, Hq, false, splits, head_dim, total_kv, Hkv).total;
 }
 
 int mtfm_hta_pw_fwd(const void* q, const void* k, const void* v, void* out, const int32_t* q_offsets,
@@ -443,7 +491,7 @@ size_t mtfm_hta_pw_workspace_bytes_rt(int layer, int dtype, int is_bwd, int32_t 
     if (check_scalars(layer, dtype, batch, total_q, total_kv, max_hist, max_rt, max_targets, Hq, Hkv, head_dim) != MTFM_HTA_OK)
         return (size_t)-1;
     const int splits = is_bwd ? 1 : forward_splits(dtype, layer, batch, max_hist, max_rt, max_targets, Hq, Hkv, head_dim);
-    return plan_workspace(dtype, is_bwd, batch, total_q, Hq, true, splits, head_dim).total;
+    return plan_workspace(dtype, is_bwd, batch, total_q, Hq, true, splits, head_dim, total_kv, Hkv).total;
 }
 
 int mtfm_hta_pw_fwd_rt(const void* q, const void* k, const void* v, void* out, const int32_t* q_offsets,

@@ -66,6 +66,11 @@ hipError_t launch_bwd_fp32(const Params& p, hipStream_t s);
 hipError_t launch_fwd_bf16(const Params& p, hipStream_t s);
 hipError_t launch_bwd_bf16(const Params& p, hipStream_t s);
 bool bf16_supported(int32_t d, int32_t Hq, int32_t Hkv);
+// bf16 rows of 16 features <-> rows of 32 with a zero upper half ([n_rows][16] and [n_rows][32], 16-byte aligned): how
+// head_dim 16 rides the 32-wide matrix tiles
+constexpr int32_t BF16_PADDED_FROM = 16, BF16_PADDED_TO = 32;
+hipError_t launch_widen16(const void* src, void* dst, int64_t n_rows, hipStream_t s);
+hipError_t launch_narrow16(const void* src, void* dst, int64_t n_rows, hipStream_t s);
 // number of key splits the bf16 forward pass uses for these host-known bounds (1 = none); decides the workspace too
 int fwd_key_splits(int32_t batch, int32_t Hq, int32_t Hkv, int32_t d, int64_t max_rows, int64_t max_keys);
 // stores the calling thread's error message (what mtfm_hta_last_error() returns) and hands `code` back

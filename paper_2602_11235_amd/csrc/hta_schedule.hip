@@ -91,7 +91,34 @@ __global__ __launch_bounds__(256) void rt_limits_kernel(Params p) {
     p.lim[(int64_t)p.q_off[b] + row] = L + lo;
 }
 
+// bf16 heads of 16 features ride the 32-wide matrix tiles zero-padded: rows [n][16] <-> [n][32] with the upper half
+// zero (one thread per 16-byte chunk).  Zero features change no score and no gradient of the features that exist.
+__global__ __launch_bounds__(256) void widen16_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, int64_t n_rows) {
+    const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;  // chunk of the wide row
+    if (id >= n_rows * 4) return;
+    const int64_t row = id >> 2;
+    const int c = (int)(id & 3);
+    dst[id] = c < 2 ? src[row * 2 + c] : uint4{0u, 0u, 0u, 0u};
+}
+__global__ __launch_bounds__(256) void narrow16_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, int64_t n_rows) {
+    const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;  // chunk of the narrow row
+    if (id >= n_rows * 2) return;
+    dst[id] = src[(id >> 1) * 4 + (id & 1)];
+}
+
 }  // namespace
+
+hipError_t launch_widen16(const void* src, void* dst, int64_t n_rows, hipStream_t s) {
+    if (n_rows <= 0) return hipSuccess;
+    hipLaunchKernelGGL(widen16_kernel, dim3((unsigned)((n_rows * 4 + 255) / 256)), dim3(256), 0, s, (const uint4*)src, (uint4*)dst, n_rows);
+    return hipGetLastError();
+}
+
+hipError_t launch_narrow16(const void* src, void* dst, int64_t n_rows, hipStream_t s) {
+    if (n_rows <= 0) return hipSuccess;
+    hipLaunchKernelGGL(narrow16_kernel, dim3((unsigned)((n_rows * 2 + 255) / 256)), dim3(256), 0, s, (const uint4*)src, (uint4*)dst, n_rows);
+    return hipGetLastError();
+}
 
 hipError_t launch_rt_limits(const Params& p, hipStream_t s) {
     const int64_t rows = max_query_rows(p);

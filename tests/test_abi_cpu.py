@@ -46,6 +46,18 @@ def test_workspace_bytes_is_host_arithmetic():
         hta.mtfm_hta_workspace_bytes(hta.LAYER_FULL, hta.BF16, True, 4, 1000, 1000, 512, 64, 8, 3, 64)
 
 
+def test_workspace_of_16_wide_bf16_heads_holds_the_padded_copies():
+    # a 16-wide head runs on the 32-wide kernels over zero-padded copies: the workspace is that of head_dim 32 plus
+    # q, out (and dout, dq) of [total_q][Hq][32] bf16 and k, v (and dk, dv) of [total_kv][Hkv][32] bf16
+    align = lambda n: (n + 255) // 256 * 256
+    tq, tkv, Hq, Hkv = 1000, 900, 8, 2
+    for layer in (hta.LAYER_FULL, hta.LAYER_TARGET):
+        for is_bwd, copies in ((False, 2), (True, 4)):
+            at32 = hta.mtfm_hta_workspace_bytes(layer, hta.BF16, is_bwd, 4, tq, tkv, 512, 64, Hq, Hkv, 32)
+            at16 = hta.mtfm_hta_workspace_bytes(layer, hta.BF16, is_bwd, 4, tq, tkv, 512, 64, Hq, Hkv, 16)
+            assert at16 == at32 + copies * (align(tq * Hq * 64) + align(tkv * Hkv * 64))
+
+
 @pytest.mark.parametrize("kwargs,status", [
     (dict(Hq=8, Hkv=3), hta.ERR_INVALID_ARG),
     (dict(head_dim=48), hta.ERR_UNSUPPORTED),

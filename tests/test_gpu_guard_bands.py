@@ -102,7 +102,8 @@ def case_of(layer, Hq, Hkv, d, dtype, rt=False, seed=91, hist=EDGE_HIST, tgts=ED
 @pytest.mark.parametrize("layer", [FULL, TARGET])
 @pytest.mark.parametrize("rt", [False, True])
 @pytest.mark.parametrize("Hq,Hkv,d,dtype", [(8, 2, 64, "bf16"), (16, 2, 128, "bf16"), (4, 2, 32, "bf16"),
-                                            (3, 1, 64, "bf16"), (16, 1, 64, "bf16"), (6, 2, 24, "fp32")])
+                                            (3, 1, 64, "bf16"), (16, 1, 64, "bf16"), (6, 2, 24, "fp32"),
+                                            (4, 1, 16, "bf16")])
 def test_attention_edge_batches_stay_inside_their_buffers(layer, rt, Hq, Hkv, d, dtype):
     run_attention(case_of(layer, Hq, Hkv, d, dtype, rt))
 

@@ -39,7 +39,7 @@ EDGE_TGTS = [3, 0, 70, 1, 33, 2, 64, 0, 129]
 
 @pytest.mark.parametrize("layer", [FULL, TARGET])
 @pytest.mark.parametrize("Hq,Hkv,d", [(8, 2, 64), (4, 4, 64), (3, 1, 64), (16, 2, 128), (16, 1, 64), (4, 2, 32),
-                                      (6, 1, 128)])
+                                      (6, 1, 128), (4, 1, 16), (8, 2, 16)])
 def test_bf16_edge_cases_forward(layer, Hq, Hkv, d):
     c = custom(f"bf16_edges_{Hq}_{Hkv}_{d}", layer, EDGE_HIST, EDGE_TGTS, Hq, Hkv, d, "bf16")
     check_case(c, with_bwd=False)
@@ -76,7 +76,8 @@ def test_bf16_large_logits_backward_on_tensor_scale():
 
 # ------------------------------------------------------------------------------ bf16 backward
 @pytest.mark.parametrize("layer", [FULL, TARGET])
-@pytest.mark.parametrize("Hq,Hkv,d", [(8, 2, 64), (4, 4, 64), (3, 1, 64), (16, 2, 128), (4, 2, 32)])
+@pytest.mark.parametrize("Hq,Hkv,d", [(8, 2, 64), (4, 4, 64), (3, 1, 64), (16, 2, 128), (4, 2, 32), (4, 1, 16),
+                                      (8, 2, 16)])
 def test_bf16_edge_cases_backward(layer, Hq, Hkv, d):
     c = custom(f"bf16_bwd_edges_{Hq}_{Hkv}_{d}", layer, EDGE_HIST, EDGE_TGTS, Hq, Hkv, d, "bf16")
     check_case(c, with_bwd=True)

@@ -100,7 +100,8 @@ def test_fp32_edge_cases(layer):
 
 
 @pytest.mark.parametrize("layer", [FULL, TARGET])
-@pytest.mark.parametrize("Hq,Hkv,d", [(8, 2, 64), (4, 4, 64), (3, 1, 64), (16, 2, 128), (16, 1, 64), (4, 2, 32), (6, 1, 128)])
+@pytest.mark.parametrize("Hq,Hkv,d", [(8, 2, 64), (4, 4, 64), (3, 1, 64), (16, 2, 128), (16, 1, 64), (4, 2, 32), (6, 1, 128),
+                                      (4, 1, 16)])
 def test_bf16_edge_cases(layer, Hq, Hkv, d):
     check(inputs.make_case(inputs.custom_config(f"pw_{Hq}_{Hkv}_{d}", layer, EDGE_HIST, EDGE_TGTS, Hq, Hkv, d, seed=52)))
 
@@ -118,7 +119,7 @@ def test_fp32_realtime_edge_cases(layer):
 
 
 @pytest.mark.parametrize("layer", [FULL, TARGET])
-@pytest.mark.parametrize("Hq,Hkv,d", [(8, 2, 64), (3, 1, 64), (16, 2, 128), (4, 2, 32)])
+@pytest.mark.parametrize("Hq,Hkv,d", [(8, 2, 64), (3, 1, 64), (16, 2, 128), (4, 2, 32), (4, 1, 16)])
 def test_bf16_realtime_edge_cases(layer, Hq, Hkv, d):
     check(inputs.make_case(inputs.custom_config(f"pw_rt_{Hq}_{Hkv}_{d}", layer, RT_HIST, RT_TGTS, Hq, Hkv, d, seed=55,
                                                 rt_len=RT_RT)))

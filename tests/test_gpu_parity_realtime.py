@@ -31,7 +31,8 @@ def test_fp32_realtime_edge_cases(layer):
 
 
 @pytest.mark.parametrize("layer", [FULL, TARGET])
-@pytest.mark.parametrize("Hq,Hkv,d", [(8, 2, 64), (4, 4, 64), (3, 1, 64), (16, 2, 128), (16, 1, 64), (4, 2, 32), (6, 1, 128)])
+@pytest.mark.parametrize("Hq,Hkv,d", [(8, 2, 64), (4, 4, 64), (3, 1, 64), (16, 2, 128), (16, 1, 64), (4, 2, 32), (6, 1, 128),
+                                      (4, 1, 16)])
 def test_bf16_realtime_edge_cases(layer, Hq, Hkv, d):
     check_case(custom(f"bf16_rt_edges_{Hq}_{Hkv}_{d}", layer, Hq, Hkv, d, "bf16"), with_bwd=True)
 
