@@ -229,19 +229,23 @@ __global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(Params p, int hpb, i
                 }
             }
         }
+        // Register v of the lane holds key 8 (v / 4) + 4 hf + v % 4 of the sub-tile; it is masked when that is >= the
+        // number of visible keys, written as 4 hf - visible >= -(8 (v / 4) + v % 4): one subtraction per lane and
+        // comparisons with constants, instead of sixteen lane constants kept in registers.
         if (masked) {  // per row: keys at or past the row's limit are not visible (P = 0)
             static_for<0, RB>([&](auto Rb) {
                 constexpr int rb = decltype(Rb)::value;
-                const int rel = lim[rb] - k0;
+                const int over = 4 * hf - (lim[rb] - k0);
                 static_for<0, 16>([&](auto V) {
                     constexpr int v = decltype(V)::value;
-                    S[rb][v] = (8 * (v / 4) + 4 * hf + (v % 4) >= rel) ? (PW ? PW_MASKED : -INFINITY) : S[rb][v];
+                    S[rb][v] = (over >= -(8 * (v / 4) + (v % 4))) ? (PW ? PW_MASKED : -INFINITY) : S[rb][v];
                 });
             });
         } else if (n_live < 32) {  // ragged: keys >= L_b are not visible (P = 0)
+            const int over = 4 * hf - n_live;
 #pragma unroll
             for (int v = 0; v < 16; v++) {
-                if (8 * (v / 4) + 4 * hf + (v % 4) >= n_live) {
+                if (over >= -(8 * (v / 4) + (v % 4))) {
 #pragma unroll
                     for (int rb = 0; rb < RB; rb++) S[rb][v] = PW ? PW_MASKED : -INFINITY;
                 }

@@ -27,96 +27,70 @@ namespace {
 constexpr int BN = 64;  // keys per LDS tile
 constexpr float RESCALE_SLACK = 8.f;  // log2 units a row's logits may exceed its softmax reference before a rescale
 
+// What a wave of the row-stationary forward pass keeps in registers -- the Q fragments of its RB blocks of 32 query
+// rows (one head), the running softmax state and the O^T accumulators -- and the steps on it.
+//
 // RT: the users carry real-time tokens (mask rule 2).  Their keys follow the history keys in the K/V rows and run through
 // the same tile loop; a sub-tile that reaches past the history is masked per query row with the row's limit
 // (p.lim: history + the real-time tokens strictly earlier than the row), and a real-time row gets its own key in the
 // epilogue exactly like a target row.
 //
-// SPLIT: the launch has too few (user, kv head, row tile) items to fill the chip (a handful of requests at
-// inference).  The grid gets a second dimension: workgroup (x, y) runs key tiles [y, y+1) * n_kt / n_splits of item x
-// and leaves a partial result -- its rows normalised by its own sum, in float32, with the logsumexp of its keys -- in
-// the workspace; split 0 also takes the rows' own keys.  merge_splits_kernel combines the partial results.
-//
 // PW: the pointwise reading of phi2 -- weights norm * silu(scale s) on the same tiles and mask: no running maximum, no
-// row sum, no lse; the accumulator is scaled by norm at the store.  With SPLIT the partial results are plain partial
-// sums, which the merge kernel adds up.
-template <int D, int RB, int NW, bool RT, bool SPLIT, bool PW = false>
-__global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb, int n_hc, int tpg) {
-    using ST = KvStage<D, NW>;
-    constexpr int NKS = D / 16, NDB = D / 32, NKB = BN / 32;
-    static_assert(ST::BN == BN, "tile height");
-    // NSTAGE stages of [K tile][V tile], filled by asynchronous global -> LDS copies NSTAGE-1 tiles ahead of their use
-    // (two ahead, except for d = 128 where a third stage would cost the second workgroup of the CU).  The compiler
-    // never sees a store into this array (the copies are issued from inline assembly), so it neither orders LDS reads
-    // against them nor drains them; the counted waits and barriers below do that.
-    constexpr int NSTAGE = D <= 64 ? 3 : 2, AHEAD = NSTAGE - 1;
-    __shared__ __attribute__((aligned(1024))) unsigned char smem[NSTAGE * ST::BYTES];
-
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
-    const WorkItem w = decode_work(blockIdx.x, p.batch * p.Hkv * n_hc, p.Hkv * n_hc, tpg);
-    if (!w.valid) return;
-    const int b = scheduled_user(p, w.user_slot);
-    const int g = w.y / n_hc, hc = w.y % n_hc;
-    const int L = p.hist_len[b], T = p.n_targets[b];
-    const int LK = L + (RT ? p.rt_len[b] : 0);  // keys that run through the tile loop: history, then real-time
-    const int n_rows = p.layer == 0 ? LK + T : T;
-    const int BM = (NW / hpb) * RB * 32;
-    const int tile_row0 = w.tile * BM;
-    if (tile_row0 >= n_rows) return;  // uniform for the whole workgroup
-    const int r = p.Hq / p.Hkv;
-    const int h = g * r + hc * hpb + wave % hpb;
-    const int wrow0 = tile_row0 + (wave / hpb) * (RB * 32);
-    const int tok_shift = p.layer == 0 ? 0 : LK;  // token index of query row 0
-    const int64_t q_base = p.q_off[b], kv_base = p.kv_off[b];
-    const __bf16* qg = (const __bf16*)p.q;
-    const __bf16* kg = (const __bf16*)p.k;
-    const __bf16* vg = (const __bf16*)p.v;
-    const float c2 = p.scale * LOG2E;  // logits are handled in the log2 domain
-    const float neg_c2 = -c2;
-
-    // Q fragments (B operand of S^T = K Q^T): lane = query row, 8 consecutive d values per k-step.
-    // Rows past the end of the user are clamped to the last row; their results are never stored.
-    bf16x8 qf[RB][NKS];
-    int lim[RB];  // RT: leading keys the lane's row sees
-#pragma unroll
-    for (int rb = 0; rb < RB; rb++) {
-        int row = wrow0 + rb * 32 + l32;
-        row = row < n_rows ? row : n_rows - 1;
-        const __bf16* qp = qg + ((q_base + row) * p.Hq + h) * D + 8 * hf;
-#pragma unroll
-        for (int ks = 0; ks < NKS; ks++) qf[rb][ks] = *(const bf16x8*)(qp + ks * 16);
-        lim[rb] = RT ? p.lim[q_base + row] : L;
-    }
-
+// row sum, no lse; the accumulator is scaled by norm at the store.
+template <int D, int RB, bool RT, bool PW>
+struct FwdRows {
+    static constexpr int NKS = D / 16, NDB = D / 32;
+    bf16x8 qf[RB][NKS];  // B operand of S^T = K Q^T: lane = query row, 8 consecutive d values per k-step
+    int lim[RB];         // leading keys the lane's row sees (RT; the history length otherwise)
     float m[RB], l[RB], grow_at[RB];
-    const float inv_c2 = 1.f / c2;
     floatx16 O[RB][NDB];
-#pragma unroll
-    for (int rb = 0; rb < RB; rb++) {
-        m[rb] = -INFINITY;
-        grow_at[rb] = -INFINITY;
-        l[rb] = 0.f;
-#pragma unroll
-        for (int db = 0; db < NDB; db++)
-#pragma unroll
-            for (int v = 0; v < 16; v++) O[rb][db][v] = 0.f;
+    // lane constants
+    int nat[NKS], tlo[NDB], thi[NDB];  // element offsets of the operand fragments inside a swizzled tile
+    int hf;
+    float scale, c2, inv_c2, neg_c2;   // logits are handled in the log2 domain: c2 = scale log2(e)
+
+    __device__ __forceinline__ void init_lane(const Params& p, int lane) {
+        hf = lane >> 5;
+        scale = p.scale;
+        c2 = p.scale * LOG2E;
+        inv_c2 = 1.f / c2;
+        neg_c2 = -c2;
+        natural_offsets<D>(nat, lane);
+        transposed_offsets<D>(tlo, thi, lane);
     }
 
-    const int n_kt_all = (LK + BN - 1) / BN;
-    const int split = SPLIT ? (int)blockIdx.y : 0;
-    const int t_lo = SPLIT ? split * n_kt_all / p.n_splits : 0;               // first key tile of this workgroup
-    const int n_kt = (SPLIT ? (split + 1) * n_kt_all / p.n_splits : n_kt_all) - t_lo;  // and how many it runs
-    int nat[NKS], tlo[NDB], thi[NDB];  // per-lane element offsets of the operand fragments inside a swizzled tile
-    natural_offsets<D>(nat, lane);
-    transposed_offsets<D>(tlo, thi, lane);
-    uint32_t voff[ST::COPIES];
-    ST::lane_offsets(voff, p.Hkv, wave, lane);
-    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-    const uint32_t smem_addr = lds_address(smem);
+    __device__ __forceinline__ void reset() {
+#pragma unroll
+        for (int rb = 0; rb < RB; rb++) {
+            m[rb] = -INFINITY;
+            grow_at[rb] = -INFINITY;
+            l[rb] = 0.f;
+#pragma unroll
+            for (int db = 0; db < NDB; db++)
+#pragma unroll
+                for (int v = 0; v < 16; v++) O[rb][db][v] = 0.f;
+        }
+    }
 
-    // One online-softmax step over a 32-key sub-tile that starts at key k0.  `n_live` = number of keys of the sub-tile
-    // that exist (32 except in the ragged last tile).
-    auto subtile = [&](const __bf16* Ks, const __bf16* Vs, int n_live, int k0) __attribute__((always_inline)) {  // Ks, Vs: first row of the sub-tile
+    // Q fragments of rows wrow0 .. wrow0 + 32 RB - 1 of head h.  Rows past the end of the user are clamped to the last
+    // row (n_rows >= 1); their results are never stored.
+    __device__ __forceinline__ void load_q(const Params& p, int64_t q_base, int h, int wrow0, int n_rows, int L, int lane) {
+        const int l32 = lane & 31, hf = lane >> 5;
+        const __bf16* qg = (const __bf16*)p.q;
+#pragma unroll
+        for (int rb = 0; rb < RB; rb++) {
+            int row = wrow0 + rb * 32 + l32;
+            row = row < n_rows ? row : n_rows - 1;
+            const __bf16* qp = qg + ((q_base + row) * p.Hq + h) * D + 8 * hf;
+#pragma unroll
+            for (int ks = 0; ks < NKS; ks++) qf[rb][ks] = *(const bf16x8*)(qp + ks * 16);
+            lim[rb] = RT ? p.lim[q_base + row] : L;
+        }
+    }
+
+    // One online-softmax step over a 32-key sub-tile that starts at key k0 (Ks, Vs: its first rows in LDS).  `n_live` =
+    // number of keys of the sub-tile that exist (32 except in the ragged last tile), L = history length of the user.
+    __device__ __forceinline__ void subtile(const __bf16* Ks, const __bf16* Vs, int n_live, int k0, int L) {
         const bool masked = RT && k0 + 32 > L;  // uniform: the sub-tile holds real-time keys (or runs past the end)
         if (masked) {
             bool any = false;
@@ -136,19 +110,23 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb,
 #pragma unroll
             for (int rb = 0; rb < RB; rb++) S[rb] = mfma32(kf, qf[rb][ks], S[rb]);
         }
+        // Register v of the lane holds key 8 (v / 4) + 4 hf + v % 4 of the sub-tile; it is masked when that is >= the
+        // number of visible keys, written as 4 hf - visible >= -(8 (v / 4) + v % 4): one subtraction per lane and
+        // comparisons with constants, instead of sixteen lane constants kept in registers.
         if (masked) {  // per row: keys at or past the row's limit are not visible
             static_for<0, RB>([&](auto Rb) {
                 constexpr int rb = decltype(Rb)::value;
-                const int rel = lim[rb] - k0;
+                const int over = 4 * hf - (lim[rb] - k0);
                 static_for<0, 16>([&](auto V) {
                     constexpr int v = decltype(V)::value;
-                    S[rb][v] = (8 * (v / 4) + 4 * hf + (v % 4) >= rel) ? (PW ? PW_MASKED : -INFINITY) : S[rb][v];
+                    S[rb][v] = (over >= -(8 * (v / 4) + (v % 4))) ? (PW ? PW_MASKED : -INFINITY) : S[rb][v];
                 });
             });
         } else if (n_live < 32) {  // ragged: keys >= L_b are not visible
+            const int over = 4 * hf - n_live;
 #pragma unroll
             for (int v = 0; v < 16; v++) {
-                if (8 * (v / 4) + 4 * hf + (v % 4) >= n_live) {
+                if (over >= -(8 * (v / 4) + (v % 4))) {
 #pragma unroll
                     for (int rb = 0; rb < RB; rb++) S[rb][v] = PW ? PW_MASKED : -INFINITY;
                 }
@@ -160,45 +138,45 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb,
             for (int rb = 0; rb < RB; rb++)
 #pragma unroll
                 for (int v = 0; v < 16; v++)
-                    pf[rb][v / 8][v % 8] = (__bf16)pw_silu(S[rb][v] * p.scale, pw_sigmoid(S[rb][v], neg_c2));
+                    pf[rb][v / 8][v % 8] = (__bf16)pw_silu(S[rb][v] * scale, pw_sigmoid(S[rb][v], neg_c2));
         } else {
-        // Online softmax, one query row per lane (two lanes, 32 apart, share a row).  The reference m[rb]
-        // of a row only has to bound its logits from above up to a factor 2^RESCALE_SLACK: weights are
-        // exp2(s - m) <= 2^RESCALE_SLACK, sums and outputs share the reference, and the final division by l
-        // removes it.  So the accumulators are rescaled only when some row of the wave outgrows the slack,
-        // which after the first tiles almost never happens.
+            // Online softmax, one query row per lane (two lanes, 32 apart, share a row).  The reference m[rb]
+            // of a row only has to bound its logits from above up to a factor 2^RESCALE_SLACK: weights are
+            // exp2(s - m) <= 2^RESCALE_SLACK, sums and outputs share the reference, and the final division by l
+            // removes it.  So the accumulators are rescaled only when some row of the wave outgrows the slack,
+            // which after the first tiles almost never happens.
 #pragma unroll
-        for (int rb = 0; rb < RB; rb++) {
-            float mx = S[rb][0];
+            for (int rb = 0; rb < RB; rb++) {
+                float mx = S[rb][0];
 #pragma unroll
-            for (int v = 1; v < 16; v++) mx = fmaxf(mx, S[rb][v]);
-            // The two lanes of a row (32 apart) each hold half of its keys: as long as neither half outgrows the
-            // row's reference by more than the slack -- tested on the raw dot products against grow_at[rb] =
-            // (m + slack) / c2 -- they need not even exchange their maxima.
-            if (__builtin_amdgcn_ballot_w64(mx > grow_at[rb]) != 0) {
-                mx = fmaxf(mx, other_half(mx)) * c2;
-                const bool grow = mx > m[rb] + RESCALE_SLACK;
-                const float m_new = grow ? mx : m[rb];
-                // 1 for the rows that keep their reference (which may still be -inf when rows see different keys)
-                const float alpha = grow ? fast_exp2(m[rb] - m_new) : 1.f;
-                m[rb] = m_new;
-                grow_at[rb] = (m_new + RESCALE_SLACK) * inv_c2;
-                l[rb] *= alpha;
+                for (int v = 1; v < 16; v++) mx = fmaxf(mx, S[rb][v]);
+                // The two lanes of a row (32 apart) each hold half of its keys: as long as neither half outgrows the
+                // row's reference by more than the slack -- tested on the raw dot products against grow_at[rb] =
+                // (m + slack) / c2 -- they need not even exchange their maxima.
+                if (__builtin_amdgcn_ballot_w64(mx > grow_at[rb]) != 0) {
+                    mx = fmaxf(mx, other_half(mx)) * c2;
+                    const bool grow = mx > m[rb] + RESCALE_SLACK;
+                    const float m_new = grow ? mx : m[rb];
+                    // 1 for the rows that keep their reference (which may still be -inf when rows see different keys)
+                    const float alpha = grow ? fast_exp2(m[rb] - m_new) : 1.f;
+                    m[rb] = m_new;
+                    grow_at[rb] = (m_new + RESCALE_SLACK) * inv_c2;
+                    l[rb] *= alpha;
 #pragma unroll
-                for (int db = 0; db < NDB; db++)
+                    for (int db = 0; db < NDB; db++)
 #pragma unroll
-                    for (int v = 0; v < 16; v++) O[rb][db][v] *= alpha;
+                        for (int v = 0; v < 16; v++) O[rb][db][v] *= alpha;
+                }
+                // (a row that has seen no key yet has the reference -inf and only masked logits: keep -inf - -inf out)
+                const float mref = RT ? fmaxf(m[rb], -1e30f) : m[rb];
+#pragma unroll
+                for (int v = 0; v < 16; v++) pf[rb][v / 8][v % 8] = (__bf16)fast_exp2(fmaf(S[rb][v], c2, -mref));
+                // the row sum uses the same rounded weights as the P V product
+                float l0 = l[rb], l1 = 0.f;
+                add_bf16x8(l0, l1, pf[rb][0]);
+                add_bf16x8(l0, l1, pf[rb][1]);
+                l[rb] = l0 + l1;
             }
-            // (a row that has seen no key yet has the reference -inf and only masked logits: keep -inf - -inf out)
-            const float mref = RT ? fmaxf(m[rb], -1e30f) : m[rb];
-#pragma unroll
-            for (int v = 0; v < 16; v++) pf[rb][v / 8][v % 8] = (__bf16)fast_exp2(fmaf(S[rb][v], c2, -mref));
-            // the row sum uses the same rounded weights as the P V product
-            float l0 = l[rb], l1 = 0.f;
-            add_bf16x8(l0, l1, pf[rb][0]);
-            add_bf16x8(l0, l1, pf[rb][1]);
-            l[rb] = l0 + l1;
-        }
         }
         // O^T[d][row] += sum_key V[key][d] P^T[key][row]
 #pragma unroll
@@ -209,7 +187,154 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb,
 #pragma unroll
                 for (int rb = 0; rb < RB; rb++) O[rb][db] = mfma32(vf, pf[rb][s2], O[rb][db]);
             }
-    };
+    }
+
+    // the 64-key tile at Ks / Vs whose first key is k0, of a user with LK keys in the tile loop and L history keys
+    // the 64-key tile at Ks / Vs whose first key is k0, of a user with LK keys in the tile loop and L history keys
+    __device__ __forceinline__ void tile(const __bf16* Ks, const __bf16* Vs, int k0, int LK, int L) {
+#pragma unroll
+        for (int kb = 0; kb < BN / 32; kb++) {
+            const int n_live = LK - k0 - kb * 32;
+            if (n_live > 0) subtile(Ks + kb * 32 * D, Vs + kb * 32 * D, n_live, k0 + kb * 32, L);
+        }
+    }
+
+    // own key of target rows (rule 3) and of real-time rows: one more online-softmax step, straight from global memory
+    __device__ __forceinline__ void own_key(const Params& p, int64_t kv_base, int g, int wrow0, int n_rows, int tok_shift, int L,
+                                            int lane) {
+        const int l32 = lane & 31, hf = lane >> 5;
+        const __bf16* kg = (const __bf16*)p.k;
+        const __bf16* vg = (const __bf16*)p.v;
+#pragma unroll
+        for (int rb = 0; rb < RB; rb++) {
+            const int row = wrow0 + rb * 32 + l32;
+            const int tok = tok_shift + row;
+            if (row < n_rows && tok >= L) {
+                const int64_t off = ((kv_base + tok) * p.Hkv + g) * D;
+                const __bf16* kp = kg + off + 8 * hf;
+                float dot = 0.f;
+#pragma unroll
+                for (int ks = 0; ks < NKS; ks++) {
+                    const bf16x8 kk = *(const bf16x8*)(kp + ks * 16);
+#pragma unroll
+                    for (int j = 0; j < 8; j++) dot = fmaf((float)qf[rb][ks][j], (float)kk[j], dot);
+                }
+                dot += other_half(dot);
+                float alpha = 1.f, ps;
+                if constexpr (PW) {
+                    ps = pw_silu(dot * scale, pw_sigmoid(dot, neg_c2));
+                } else {
+                    const float s2 = dot * c2;
+                    const float m_new = fmaxf(m[rb], s2);
+                    alpha = fast_exp2(m[rb] - m_new);
+                    ps = fast_exp2(s2 - m_new);
+                    m[rb] = m_new;
+                    l[rb] = l[rb] * alpha + (hf == 0 ? ps : 0.f);
+                }
+#pragma unroll
+                for (int db = 0; db < NDB; db++)
+#pragma unroll
+                    for (int v4 = 0; v4 < 4; v4++) {
+                        const bf16x4 vv = *(const bf16x4*)(vg + off + db * 32 + 8 * v4 + 4 * hf);
+#pragma unroll
+                        for (int j = 0; j < 4; j++) O[rb][db][4 * v4 + j] = fmaf(O[rb][db][4 * v4 + j], alpha, ps * (float)vv[j]);
+                    }
+            }
+        }
+    }
+
+    // normalisation and stores.  SPLIT: the partial result of key split `split` -- rows normalised by their own sum
+    // (0 when the split saw no key: lse = -inf), float32, with the logsumexp of its keys -- goes to the workspace.
+    template <bool SPLIT>
+    __device__ __forceinline__ void store(const Params& p, int64_t q_base, int h, int wrow0, int n_rows, int split, int lane) {
+        const int l32 = lane & 31, hf = lane >> 5;
+#pragma unroll
+        for (int rb = 0; rb < RB; rb++) {
+            const int row = wrow0 + rb * 32 + l32;
+            const bool live = row < n_rows;
+            const float lt = l[rb] + other_half(l[rb]);
+            if (live && SPLIT) {
+                const float inv = PW ? p.norm : (lt > 0.f ? 1.f / lt : 0.f);
+                float* op = p.o_part + (((int64_t)split * p.total_q + q_base + row) * p.Hq + h) * D;
+#pragma unroll
+                for (int db = 0; db < NDB; db++)
+#pragma unroll
+                    for (int v4 = 0; v4 < 4; v4++) {
+                        floatx4 o4;
+#pragma unroll
+                        for (int j = 0; j < 4; j++) o4[j] = O[rb][db][4 * v4 + j] * inv;
+                        *(floatx4*)(op + db * 32 + 8 * v4 + 4 * hf) = o4;
+                    }
+                if (!PW && hf == 0)
+                    p.lse_part[((int64_t)split * p.Hq + h) * p.total_q + q_base + row] =
+                        lt > 0.f ? (m[rb] + __builtin_amdgcn_logf(lt)) * LN2 : -INFINITY;
+            } else if (live) {
+                const float inv = PW ? p.norm : 1.f / lt;
+                __bf16* op = (__bf16*)p.out + ((q_base + row) * p.Hq + h) * D;
+#pragma unroll
+                for (int db = 0; db < NDB; db++)
+#pragma unroll
+                    for (int v4 = 0; v4 < 4; v4++) {
+                        bf16x4 o4;
+#pragma unroll
+                        for (int j = 0; j < 4; j++) o4[j] = (__bf16)(O[rb][db][4 * v4 + j] * inv);
+                        *(bf16x4*)(op + db * 32 + 8 * v4 + 4 * hf) = o4;
+                    }
+                if (!PW && hf == 0) p.lse[(int64_t)h * p.total_q + q_base + row] = (m[rb] + __builtin_amdgcn_logf(lt)) * LN2;
+            }
+        }
+    }
+};
+
+// One workgroup per (user, kv head, chunk of query heads, tile of BM rows), from the launch grid.
+//
+// SPLIT: the launch has too few (user, kv head, row tile) items to fill the chip (a handful of requests at
+// inference).  The grid gets a second dimension: workgroup (x, y) runs key tiles [y, y+1) * n_kt / n_splits of item x
+// and leaves a partial result in the workspace; split 0 also takes the rows' own keys.  merge_splits_kernel combines
+// the partial results (with PW they are plain partial sums, which it adds up).
+template <int D, int RB, int NW, bool RT, bool SPLIT, bool PW = false>
+__global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb, int n_hc, int tpg) {
+    using ST = KvStage<D, NW>;
+    static_assert(ST::BN == BN, "tile height");
+    // NSTAGE stages of [K tile][V tile], filled by asynchronous global -> LDS copies NSTAGE-1 tiles ahead of their use
+    // (two ahead, except for d = 128 where a third stage would cost the second workgroup of the CU).  The compiler
+    // never sees a store into this array (the copies are issued from inline assembly), so it neither orders LDS reads
+    // against them nor drains them; the counted waits and barriers below do that.
+    constexpr int NSTAGE = D <= 64 ? 3 : 2, AHEAD = NSTAGE - 1;
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[NSTAGE * ST::BYTES];
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const WorkItem w = decode_work(blockIdx.x, p.batch * p.Hkv * n_hc, p.Hkv * n_hc, tpg);
+    if (!w.valid) return;
+    const int b = scheduled_user(p, w.user_slot);
+    const int g = w.y / n_hc, hc = w.y % n_hc;
+    const int L = p.hist_len[b], T = p.n_targets[b];
+    const int LK = L + (RT ? p.rt_len[b] : 0);  // keys that run through the tile loop: history, then real-time
+    const int n_rows = p.layer == 0 ? LK + T : T;
+    const int BM = (NW / hpb) * RB * 32;
+    const int tile_row0 = w.tile * BM;
+    if (tile_row0 >= n_rows) return;  // uniform for the whole workgroup
+    const int r = p.Hq / p.Hkv;
+    const int h = g * r + hc * hpb + wave % hpb;
+    const int wrow0 = tile_row0 + (wave / hpb) * (RB * 32);
+    const int tok_shift = p.layer == 0 ? 0 : LK;  // token index of query row 0
+    const int64_t q_base = p.q_off[b], kv_base = p.kv_off[b];
+    const __bf16* kg = (const __bf16*)p.k;
+    const __bf16* vg = (const __bf16*)p.v;
+
+    FwdRows<D, RB, RT, PW> rows;
+    rows.init_lane(p, lane);
+    rows.load_q(p, q_base, h, wrow0, n_rows, L, lane);
+    rows.reset();
+
+    const int n_kt_all = (LK + BN - 1) / BN;
+    const int split = SPLIT ? (int)blockIdx.y : 0;
+    const int t_lo = SPLIT ? split * n_kt_all / p.n_splits : 0;               // first key tile of this workgroup
+    const int n_kt = (SPLIT ? (split + 1) * n_kt_all / p.n_splits : n_kt_all) - t_lo;  // and how many it runs
+    uint32_t voff[ST::COPIES];
+    ST::lane_offsets(voff, p.Hkv, wave, lane);
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const uint32_t smem_addr = lds_address(smem);
 
     // The first tiles are requested while the Q fragments are still on their way: one memory latency instead of two
     // at the start of every workgroup.  From the wait on, the only vector-memory traffic of the loop are the
@@ -226,13 +351,7 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb,
         if (t + AHEAD < n_kt)
             ST::issue(kg, vg, kv_base, p.Hkv, g, LK, t_lo + t + AHEAD, smem_addr + ((st + AHEAD) % NSTAGE) * ST::BYTES, voff, wave_u, lane);
         const __bf16* Ks = (const __bf16*)(smem + st * ST::BYTES);
-        const __bf16* Vs = Ks + ST::TILE;
-        const int live = LK - (t_lo + t) * BN;  // keys of this tile that exist (>= 1)
-#pragma unroll
-        for (int kb = 0; kb < NKB; kb++) {
-            const int n_live = live - kb * 32;
-            if (n_live > 0) subtile(Ks + kb * 32 * D, Vs + kb * 32 * D, n_live, (t_lo + t) * BN + kb * 32);
-        }
+        rows.tile(Ks, Ks + ST::TILE, (t_lo + t) * BN, LK, L);
         // tile t+1 must have landed; a tile requested after it may stay in flight
         if (AHEAD > 1 && t + 2 < n_kt) wait_vmem_outstanding<ST::COPIES>(); else wait_vmem_outstanding<0>();
         lds_barrier();
@@ -245,76 +364,8 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(Params p, int hpb,
         }
     }
 
-    // epilogue: own key of target rows (rule 3) and of real-time rows, normalisation, stores
-    __bf16* og = (__bf16*)p.out;
-#pragma unroll
-    for (int rb = 0; rb < RB; rb++) {
-        const int row = wrow0 + rb * 32 + l32;
-        const bool live = row < n_rows;
-        const int tok = tok_shift + row;
-        if (live && tok >= L && split == 0) {
-            const int64_t off = ((kv_base + tok) * p.Hkv + g) * D;
-            const __bf16* kp = kg + off + 8 * hf;
-            float dot = 0.f;
-#pragma unroll
-            for (int ks = 0; ks < NKS; ks++) {
-                const bf16x8 kk = *(const bf16x8*)(kp + ks * 16);
-#pragma unroll
-                for (int j = 0; j < 8; j++) dot = fmaf((float)qf[rb][ks][j], (float)kk[j], dot);
-            }
-            dot += other_half(dot);
-            float alpha = 1.f, ps;
-            if constexpr (PW) {
-                ps = pw_silu(dot * p.scale, pw_sigmoid(dot, neg_c2));
-            } else {
-                const float s2 = dot * c2;
-                const float m_new = fmaxf(m[rb], s2);
-                alpha = fast_exp2(m[rb] - m_new);
-                ps = fast_exp2(s2 - m_new);
-                m[rb] = m_new;
-                l[rb] = l[rb] * alpha + (hf == 0 ? ps : 0.f);
-            }
-#pragma unroll
-            for (int db = 0; db < NDB; db++)
-#pragma unroll
-                for (int v4 = 0; v4 < 4; v4++) {
-                    const bf16x4 vv = *(const bf16x4*)(vg + off + db * 32 + 8 * v4 + 4 * hf);
-#pragma unroll
-                    for (int j = 0; j < 4; j++) O[rb][db][4 * v4 + j] = fmaf(O[rb][db][4 * v4 + j], alpha, ps * (float)vv[j]);
-                }
-        }
-        const float lt = l[rb] + other_half(l[rb]);
-        if (live && SPLIT) {
-            // partial result of this split: rows normalised by their own sum (0 when the split saw no key: lse = -inf)
-            const float inv = PW ? p.norm : (lt > 0.f ? 1.f / lt : 0.f);
-            float* op = p.o_part + (((int64_t)split * p.total_q + q_base + row) * p.Hq + h) * D;
-#pragma unroll
-            for (int db = 0; db < NDB; db++)
-#pragma unroll
-                for (int v4 = 0; v4 < 4; v4++) {
-                    floatx4 o4;
-#pragma unroll
-                    for (int j = 0; j < 4; j++) o4[j] = O[rb][db][4 * v4 + j] * inv;
-                    *(floatx4*)(op + db * 32 + 8 * v4 + 4 * hf) = o4;
-                }
-            if (!PW && hf == 0)
-                p.lse_part[((int64_t)split * p.Hq + h) * p.total_q + q_base + row] =
-                    lt > 0.f ? (m[rb] + __builtin_amdgcn_logf(lt)) * LN2 : -INFINITY;
-        } else if (live) {
-            const float inv = PW ? p.norm : 1.f / lt;
-            __bf16* op = og + ((q_base + row) * p.Hq + h) * D;
-#pragma unroll
-            for (int db = 0; db < NDB; db++)
-#pragma unroll
-                for (int v4 = 0; v4 < 4; v4++) {
-                    bf16x4 o4;
-#pragma unroll
-                    for (int j = 0; j < 4; j++) o4[j] = (__bf16)(O[rb][db][4 * v4 + j] * inv);
-                    *(bf16x4*)(op + db * 32 + 8 * v4 + 4 * hf) = o4;
-                }
-            if (!PW && hf == 0) p.lse[(int64_t)h * p.total_q + q_base + row] = (m[rb] + __builtin_amdgcn_logf(lt)) * LN2;
-        }
-    }
+    if (split == 0) rows.own_key(p, kv_base, g, wrow0, n_rows, tok_shift, L, lane);
+    rows.template store<SPLIT>(p, q_base, h, wrow0, n_rows, split, lane);
 }
 
 // out = sum_s w_s O_s / sum_s w_s with w_s = exp(lse_s - max lse), lse = max lse + log sum_s w_s: the exact
