@@ -42,18 +42,17 @@ struct FwdRows {
     static constexpr int NKS = D / 16, NDB = D / 32;
     bf16x8 qf[RB][NKS];  // B operand of S^T = K Q^T: lane = query row, 8 consecutive d values per k-step
     int lim[RB];         // leading keys the lane's row sees (RT; the history length otherwise)
-    float m[RB], l[RB], grow_at[RB];
+    float m[RB], l[RB];
     floatx16 O[RB][NDB];
     // lane constants
     int nat[NKS], tlo[NDB], thi[NDB];  // element offsets of the operand fragments inside a swizzled tile
     int hf;
-    float scale, c2, inv_c2, neg_c2;   // logits are handled in the log2 domain: c2 = scale log2(e)
+    float scale, c2, neg_c2;   // logits are handled in the log2 domain: c2 = scale log2(e)
 
     __device__ __forceinline__ void init_lane(const Params& p, int lane) {
         hf = lane >> 5;
         scale = p.scale;
         c2 = p.scale * LOG2E;
-        inv_c2 = 1.f / c2;
         neg_c2 = -c2;
         natural_offsets<D>(nat, lane);
         transposed_offsets<D>(tlo, thi, lane);
@@ -63,7 +62,6 @@ struct FwdRows {
 #pragma unroll
         for (int rb = 0; rb < RB; rb++) {
             m[rb] = -INFINITY;
-            grow_at[rb] = -INFINITY;
             l[rb] = 0.f;
 #pragma unroll
             for (int db = 0; db < NDB; db++)
@@ -141,42 +139,48 @@ struct FwdRows {
                     pf[rb][v / 8][v % 8] = (__bf16)pw_silu(S[rb][v] * scale, pw_sigmoid(S[rb][v], neg_c2));
         } else {
             // Online softmax, one query row per lane (two lanes, 32 apart, share a row).  The reference m[rb]
-            // of a row only has to bound its logits from above up to a factor 2^RESCALE_SLACK: weights are
-            // exp2(s - m) <= 2^RESCALE_SLACK, sums and outputs share the reference, and the final division by l
-            // removes it.  So the accumulators are rescaled only when some row of the wave outgrows the slack,
-            // which after the first tiles almost never happens.
+            // of a row only has to bound its logits from above up to a modest factor: weights are exp2(s - m), sums
+            // and outputs share the reference, and the final division by l removes it.  So the weights are formed
+            // against the reference as it stands, without looking for the maximum first; the lane's sum of its 16
+            // weights tells whether that was good enough: at most SUM_CAP = 16 * 2^RESCALE_SLACK when no logit exceeds
+            // the reference by more than the slack (and inf or NaN while the reference is still -inf).  Only when some
+            // lane of the wave fails that test -- in the first sub-tile of a row, and the handful of times a row
+            // outgrows its reference -- is the maximum taken, the reference raised, the accumulators rescaled and
+            // the weights formed again.  (The sum uses the rounded weights, the same as the P V product.)
+            constexpr float SUM_CAP = 4096.f;
+            static_assert(RESCALE_SLACK == 8.f, "SUM_CAP is 16 * 2^RESCALE_SLACK");
+            static_for<0, RB>([&](auto Rb) {
+                constexpr int rb = decltype(Rb)::value;
+                auto weights = [&](float ref) __attribute__((always_inline)) {
 #pragma unroll
-            for (int rb = 0; rb < RB; rb++) {
-                float mx = S[rb][0];
+                    for (int v = 0; v < 16; v++) pf[rb][v / 8][v % 8] = (__bf16)fast_exp2(fmaf(S[rb][v], c2, -ref));
+                    float s0 = 0.f, s1 = 0.f;
+                    add_bf16x8(s0, s1, pf[rb][0]);
+                    add_bf16x8(s0, s1, pf[rb][1]);
+                    return s0 + s1;
+                };
+                // (a row that has seen no key yet has the reference -inf: with real-time masks it may hold only masked
+                // logits; keep -inf - -inf out)
+                float lt = weights(RT ? fmaxf(m[rb], -1e30f) : m[rb]);
+                if (__builtin_amdgcn_ballot_w64(!(lt <= SUM_CAP)) != 0) {
+                    float mx = S[rb][0];
 #pragma unroll
-                for (int v = 1; v < 16; v++) mx = fmaxf(mx, S[rb][v]);
-                // The two lanes of a row (32 apart) each hold half of its keys: as long as neither half outgrows the
-                // row's reference by more than the slack -- tested on the raw dot products against grow_at[rb] =
-                // (m + slack) / c2 -- they need not even exchange their maxima.
-                if (__builtin_amdgcn_ballot_w64(mx > grow_at[rb]) != 0) {
+                    for (int v = 1; v < 16; v++) mx = fmaxf(mx, S[rb][v]);
                     mx = fmaxf(mx, other_half(mx)) * c2;
                     const bool grow = mx > m[rb] + RESCALE_SLACK;
                     const float m_new = grow ? mx : m[rb];
                     // 1 for the rows that keep their reference (which may still be -inf when rows see different keys)
                     const float alpha = grow ? fast_exp2(m[rb] - m_new) : 1.f;
                     m[rb] = m_new;
-                    grow_at[rb] = (m_new + RESCALE_SLACK) * inv_c2;
                     l[rb] *= alpha;
 #pragma unroll
                     for (int db = 0; db < NDB; db++)
 #pragma unroll
                         for (int v = 0; v < 16; v++) O[rb][db][v] *= alpha;
+                    lt = weights(RT ? fmaxf(m_new, -1e30f) : m_new);
                 }
-                // (a row that has seen no key yet has the reference -inf and only masked logits: keep -inf - -inf out)
-                const float mref = RT ? fmaxf(m[rb], -1e30f) : m[rb];
-#pragma unroll
-                for (int v = 0; v < 16; v++) pf[rb][v / 8][v % 8] = (__bf16)fast_exp2(fmaf(S[rb][v], c2, -mref));
-                // the row sum uses the same rounded weights as the P V product
-                float l0 = l[rb], l1 = 0.f;
-                add_bf16x8(l0, l1, pf[rb][0]);
-                add_bf16x8(l0, l1, pf[rb][1]);
-                l[rb] = l0 + l1;
-            }
+                l[rb] += lt;
+            });
         }
         // O^T[d][row] += sum_key V[key][d] P^T[key][row]
 #pragma unroll
