@@ -23,7 +23,8 @@ extern "C" {
  * Process-wide state; not meant to be toggled while another thread is inside a call.
  */
 enum { MTFM_HTA_KERNEL_FWD = 0,      /* forward attention kernel */
-       MTFM_HTA_KERNEL_BWD_SELF = 1, /* dk/dv of the target tokens' own keys */
+       MTFM_HTA_KERNEL_BWD_SELF = 1, /* dk/dv of the target tokens' own keys: no launch of its own any more (its blocks
+                                        ride at the end of the BWD_DQ grid), never recorded */
        MTFM_HTA_KERNEL_BWD_DQ = 2,   /* dq (row-stationary pass; the whole backward of the fp32 path) */
        MTFM_HTA_KERNEL_BWD_DKDV = 3, /* dk, dv of the history keys (key-stationary pass) */
        MTFM_HTA_N_KERNELS = 7        /* kinds 4..6 belong to mtfm_gln.h */ };

@@ -5,9 +5,10 @@
 //   P = exp(scale S - lse),  dP = dO V^T,  dS = P o (dP - delta),  delta_i = <dO_i, O_i>
 //   dV = P^T dO,  dK = scale dS^T Q  (both summed over the query heads of the kv group),  dQ = scale dS K
 //
-// Three kernels, no atomics, no float32 staging of any gradient:
+// Three pieces of work in two launches, no atomics, no float32 staging of any gradient:
 //   1. bwd_self: the self-key terms of target rows' keys (rule 3: a target key is seen by its own row
-//      only, so its dk/dv come from that row alone and are written here, final, in bf16).
+//      only, so its dk/dv come from that row alone and are written here, final, in bf16).  Its blocks
+//      are the last blocks of the dQ grid.
 //   2. bwd_dq:   row-stationary, the forward kernel's decomposition: a wave keeps query rows (Q, dO, dQ) in
 //      registers and streams the history K/V tiles through LDS.  S^T = K Q^T and dP^T = V dO^T have
 //      the query row on the lane, so lse and delta are one register each and dS^T in accumulator layout
@@ -40,16 +41,18 @@ __device__ inline float group_sum(float x, int width) {  // sum over aligned gro
 }
 
 // ---------------------------------------------------------------------------------------- self keys
-// One group of D/8 lanes per (target token, kv head); the group walks the r query heads of the kv head.
+// One group of D/8 lanes per (target token, kv head); the group walks the r query heads of the kv head.  A block of
+// THREADS threads takes the items block_x * IPB .. of user b.  HBM-bound and small (the target rows only); it has no
+// launch of its own: its blocks are the last blocks of the dQ grid, where they fill compute units that the tail of
+// that pass leaves idle.
 // PW: pointwise weights, p = norm silu(x), ds = norm dp silu'(x) scale (no lse, no delta, `out` is not read).
-template <int D, bool PW = false>
-__global__ __launch_bounds__(256) void bwd_self_kernel(Params p) {
+template <int D, bool PW, int THREADS>
+__device__ inline void bwd_self_block(const Params& p, int block_x, int b) {
     constexpr int LPR = D / 8;           // lanes per item, 8 elements (16 bytes) each
-    constexpr int IPB = 256 / LPR;       // items per block
-    const int b = blockIdx.z;  // bandwidth-bound pass: user order does not matter
+    constexpr int IPB = THREADS / LPR;   // items per block
     const int L = p.hist_len[b] + (p.rt_len ? p.rt_len[b] : 0), T = p.n_targets[b];  // L: tokens before the targets
     const int r = p.Hq / p.Hkv;
-    const int item = blockIdx.x * IPB + threadIdx.x / LPR;  // (target, g) flattened, g fastest
+    const int item = block_x * IPB + threadIdx.x / LPR;  // (target, g) flattened, g fastest
     const int sub = threadIdx.x % LPR;
     const int t = item / p.Hkv, g = item % p.Hkv;
     if (t >= T) return;  // whole lane groups leave together; group_sum only talks inside a group
@@ -119,8 +122,14 @@ constexpr int BN = 64;  // keys per LDS tile of the dQ kernel
 // tile loop, masked per query row with the row's limit; a real-time row gets its own key in the epilogue.
 // PW: the pointwise reading of phi2 -- dS = dP o silu'(scale S), scaled by norm * scale at the store; no lse, no
 // delta, `out` is not read.  The row statistics the dK/dV pass starts its accumulators from are left as zeros.
+// Blocks n_dq .. of the grid are the self-key blocks (bwd_self_block), self_bpu per user.
 template <int D, int RB, int NW, bool RT, bool PW = false>
-__global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(Params p, int hpb, int n_hc, int tpg) {
+__global__ __launch_bounds__(NW * 64, 2) void bwd_dq_kernel(Params p, int hpb, int n_hc, int tpg, unsigned n_dq, unsigned self_bpu) {
+    if (blockIdx.x >= n_dq) {  // uniform for the block, and before any barrier
+        const unsigned sb = blockIdx.x - n_dq;
+        bwd_self_block<D, PW, NW * 64>(p, (int)(sb % self_bpu), (int)(sb / self_bpu));
+        return;
+    }
     using ST = KvStage<D, NW>;
     constexpr int NKS = D / 16, NDB = D / 32, NKB = BN / 32;
     static_assert(ST::BN == BN, "tile height");
@@ -792,10 +801,15 @@ hipError_t launch_dq(const Params& p, hipStream_t s) {
     if (rows <= 0) return hipSuccess;
     const int64_t n_rt = (rows + BM - 1) / BM;
     const int64_t n_blocks = work_grid((int64_t)p.batch * p.Hkv * n_hc, n_rt);
-    if (n_blocks >= (1ll << 31)) return hipErrorInvalidValue;
+    // the self-key blocks: (target, kv head) items of every user, NW * 64 / (D / 8) per block
+    constexpr int IPB = NW * 64 / (D / 8);
+    const int64_t self_bpu = ((int64_t)p.max_targets * p.Hkv + IPB - 1) / IPB;
+    const int64_t n_self = self_bpu * p.batch;
+    if (n_blocks + n_self >= (1ll << 31)) return hipErrorInvalidValue;
     auto kernel = p.pointwise ? (p.rt_len ? bwd_dq_kernel<D, RB, NW, true, true> : bwd_dq_kernel<D, RB, NW, false, true>)
                   : p.rt_len  ? bwd_dq_kernel<D, RB, NW, true> : bwd_dq_kernel<D, RB, NW, false>;
-    hipLaunchKernelGGL(kernel, dim3((unsigned)n_blocks), dim3(NW * 64), 0, s, p, hpb, n_hc, (int)n_rt);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)(n_blocks + n_self)), dim3(NW * 64), 0, s, p, hpb, n_hc, (int)n_rt,
+                       (unsigned)n_blocks, (unsigned)(self_bpu > 0 ? self_bpu : 1));
     return hipGetLastError();
 }
 
@@ -820,32 +834,10 @@ hipError_t launch_dkdv(const Params& p, hipStream_t s) {
     return p.rt_len ? launch_dkdv_as<D, NW, true>(p, s) : launch_dkdv_as<D, NW, false>(p, s);
 }
 
-template <int D>
-hipError_t launch_self(const Params& p, hipStream_t s) {
-    if (p.max_targets <= 0) return hipSuccess;
-    constexpr int IPB = 256 / (D / 8);
-    const int64_t items = (int64_t)p.max_targets * p.Hkv;
-    dim3 grid((unsigned)((items + IPB - 1) / IPB), 1, (unsigned)p.batch);
-    if (p.pointwise)
-        hipLaunchKernelGGL((bwd_self_kernel<D, true>), grid, dim3(256), 0, s, p);
-    else
-        hipLaunchKernelGGL((bwd_self_kernel<D, false>), grid, dim3(256), 0, s, p);
-    return hipGetLastError();
-}
-
 }  // namespace
 
 hipError_t launch_bwd_bf16(const Params& p, hipStream_t s) {
     hipError_t e;
-    timing_begin(MTFM_HTA_KERNEL_BWD_SELF, s);
-    switch (p.d) {
-        case 32: e = launch_self<32>(p, s); break;
-        case 64: e = launch_self<64>(p, s); break;
-        case 128: e = launch_self<128>(p, s); break;
-        default: e = hipErrorInvalidValue;
-    }
-    timing_end(MTFM_HTA_KERNEL_BWD_SELF, s);
-    if (e != hipSuccess) return e;
     // eight waves of one row block when the head group fills them, else four waves of two
     const bool wide = ((p.Hq / p.Hkv) % 8) == 0;
     timing_begin(MTFM_HTA_KERNEL_BWD_DQ, s);
