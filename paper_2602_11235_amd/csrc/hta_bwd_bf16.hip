@@ -385,7 +385,7 @@ struct DkdvSmem {
 // RT: users with real-time tokens (mask rule 2).  Their keys follow the history keys and are owned by waves like any
 // other key; a wave whose 32 keys reach past the history takes the masked instruction stream, where a weight
 // survives only if the key lies below the row's limit (p.lim, staged with the row statistics) or is the row's own
-// token (the own key of a real-time row; target rows' own keys are the business of bwd_self_kernel).
+// token (the own key of a real-time row; target rows' own keys are the business of bwd_self_block).
 // PW: the pointwise reading of phi2 -- P = silu(scale S), dS = dP o silu'(scale S); the staged row statistics are
 // zeros for rows that exist (the sentinel for rows that do not still removes them), norm is applied at the store.
 template <int D, int NW, bool RT, bool PW = false>
