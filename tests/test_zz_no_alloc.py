@@ -53,7 +53,7 @@ def test_two_calls_in_a_row_the_second_on_a_smaller_input():
 @pytest.mark.gpu
 def test_split_forward_and_other_shapes():
     # a few requests: the keys are split and the partial results live in the built-in scratch memory; then the same
-    # call on one request with fewer, shorter splits; then the fp32 path (no scratch memory at all) and d = 128
+    # call on one request with fewer, shorter splits; then the fp32 path (no scratch memory at all), d = 128 and d = 16
     many = inputs.make_case(inputs.custom_config("static_split", TARGET, [2048, 0, 1, 63, 128, 65, 1000, 64],
                                                  [16, 5, 1, 33, 64, 2, 70, 0], 8, 2, 64, seed=63), with_dout=False)
     one = inputs.make_case(inputs.custom_config("static_split_one", TARGET, [600], [16], 8, 2, 64, seed=64),
@@ -64,6 +64,9 @@ def test_split_forward_and_other_shapes():
     check(inputs.make_case(inputs.custom_config("static_fp32", FULL, [40, 0, 64], [8, 3, 0], 4, 1, 16, dtype="fp32",
                                                 std=0.5, seed=65), with_dout=False))
     check(inputs.make_case(inputs.custom_config("static_d128", FULL, [257, 31], [129, 0], 16, 2, 128, seed=66),
+                           with_dout=False))
+    # 16-wide bf16 heads: their zero-padded copies live in the built-in scratch memory too
+    check(inputs.make_case(inputs.custom_config("static_d16", FULL, [200, 0, 65], [5, 3, 40], 4, 1, 16, seed=67),
                            with_dout=False))
 
 
