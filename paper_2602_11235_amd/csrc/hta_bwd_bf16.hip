@@ -789,6 +789,243 @@ __global__ __launch_bounds__(NW * 64, D > 64 ? 1 : 2) void bwd_dkdv_kernel(Param
     }
 }
 
+// ---------------------------------------------------------------------------------------- dK, dV: few query rows
+// The same pass for batches whose users have few query rows (a target-only layer: the candidates of a user against a
+// long history).  bwd_dkdv_kernel streams the rows of a user past every 128-key tile again; with a handful of row
+// blocks that is a prologue, a drained pipeline and an epilogue around four to eight iterations.  Here a workgroup
+// takes a whole (user, kv head): it stages ALL (head, 32-row block) units of Q and dO in LDS once (at most MAX_UNITS of
+// them, which is what the host checks), and then its waves walk the keys, 32 per wave and pass, each on its own: K/V
+// fragments from global memory, every unit from LDS, dK/dV stored -- no barrier, no copy and no counted wait inside the
+// key loop, and waves that drift apart.  Twelve waves, three per SIMD, one unit in flight per wave (168 registers):
+// measured against eight waves with two units interleaved per wave, as bwd_dkdv_kernel does it, the third wave hides
+// more than the interleaving (dK/dV of a 512 x 2048 x 128 target layer 1.21 against 1.30 ms; streaming kernel 1.33).
+// Softmax weights without real-time tokens only (the callers that need the other readings take the streaming kernel).
+template <int D, int NW>
+struct DkdvResident {
+    static constexpr int MAX_UNITS = 16;
+    static constexpr int TILE = 32 * D;                                          // elements of a 32-row tile
+    static constexpr size_t UNIT_BYTES = (size_t)2 * TILE * 2 + 2 * 32 * sizeof(float);  // Q, dO, -lse/scale[32], -delta[32]
+    static constexpr size_t BYTES = MAX_UNITS * UNIT_BYTES;
+};
+
+template <int D, int NW>
+__global__ __launch_bounds__(NW * 64, 3) void bwd_dkdv_resident_kernel(Params p, unsigned per_xcd) {
+    using SM = DkdvResident<D, NW>;
+    constexpr int NKS = D / 16, NDB = D / 32;
+    constexpr int CPR = D / 8;      // 16-byte chunks per row
+    constexpr int RPI = 64 / CPR;   // rows covered by one wave-wide 1 KB copy
+    constexpr int IPT = 32 / RPI;   // copies per tile
+    __shared__ __attribute__((aligned(1024))) unsigned char units[SM::BYTES];
+    __shared__ int s_item;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const int r = p.Hq / p.Hkv;
+    const float c2 = p.scale * LOG2E;
+
+    // per-lane element offsets into a swizzled tile (as in bwd_dkdv_kernel)
+    int nat_off[NKS], tr_lo[NDB], tr_hi[NDB];
+    natural_offsets<D>(nat_off, lane);
+    transposed_offsets<D>(tr_lo, tr_hi, lane);
+    // copy j of a tile covers rows j*RPI .. j*RPI+RPI-1: byte offset of the lane's chunk from (row0, head h)
+    uint32_t tile_voff[IPT];
+#pragma unroll
+    for (int j = 0; j < IPT; j++) {
+        const int trow = j * RPI + lane / CPR;
+        tile_voff[j] = (uint32_t)((trow * p.Hq * D + (((lane % CPR) ^ swizzle<D>(trow)) << 3)) * 2);
+    }
+
+    struct Operands {
+        bf16x8 qa[NKS], da[NKS];
+        floatx16 S, dP;  // [row (registers)][key (lanes)]
+    };
+    struct Transposed {
+        bf16x8 dot[NDB][2], qt[NDB][2];
+    };
+    struct Weights {
+        bf16x8 pb[2], dsb[2];
+    };
+
+    auto process = [&](unsigned id) {
+        const WorkItem w = decode_work(id, p.batch * p.Hkv, p.Hkv, 1);
+        if (!w.valid) return;
+        const int b = scheduled_user(p, w.user_slot), g = w.y;
+        const int LK = p.hist_len[b], T = p.n_targets[b];
+        if (LK <= 0) return;  // no key receives a gradient here
+        const int n_rows = p.layer == 0 ? LK + T : T;
+        const int n_rb = (n_rows + 31) / 32;
+        // unit u = (32-row block u / r, head g*r + u % r).  (The launch is chosen from the caller's bounds on the rows of a
+        // user; should a user exceed them, the clamp keeps the staging inside LDS.)
+        const int n_units = min(n_rb * r, SM::MAX_UNITS);
+        const int64_t q_base = p.q_off[b], kv_base = p.kv_off[b];
+
+        // ---- stage every unit: wave u % NW brings unit u (2 * IPT tile copies and the row statistics)
+        const uint32_t lds0 = lds_address(units);
+        for (int u = wave_u; u < n_units; u += NW) {
+            const int rb = u / r, h = g * r + u % r, row0 = rb * 32;
+            const uint32_t unit = lds0 + (uint32_t)u * (uint32_t)SM::UNIT_BYTES;
+            const bool whole = row0 + 32 <= n_rows;  // every row exists: no per-lane address arithmetic
+            if (whole) {
+                const int64_t ubase = ((q_base + row0) * p.Hq + h) * (int64_t)D;
+#pragma unroll
+                for (int j = 0; j < IPT; j++) {
+                    copy16_global_to_lds_at((const __bf16*)p.q + ubase, tile_voff[j], unit + (uint32_t)j * 1024u);
+                    copy16_global_to_lds_at((const __bf16*)p.dout + ubase, tile_voff[j], unit + (uint32_t)SM::TILE * 2u + (uint32_t)j * 1024u);
+                }
+                const float* stat = (hf == 0 ? p.neg_lse_s : p.neg_delta) + ((int64_t)h * p.total_q + q_base + row0 + l32);
+                copy4_global_to_lds_at(stat, unit + 4u * (uint32_t)SM::TILE);
+            } else {
+#pragma unroll
+                for (int j = 0; j < IPT; j++) {
+                    const int trow = j * RPI + lane / CPR;
+                    int row = row0 + trow;
+                    row = row < n_rows ? row : n_rows - 1;  // rows past the end repeat the last row, with no weight
+                    const int chunk = (lane % CPR) ^ swizzle<D>(trow);
+                    const int64_t off = ((q_base + row) * p.Hq + h) * D + chunk * 8;
+                    copy16_global_to_lds_at((const __bf16*)p.q + off, unit + (uint32_t)j * 1024u);
+                    copy16_global_to_lds_at((const __bf16*)p.dout + off, unit + (uint32_t)SM::TILE * 2u + (uint32_t)j * 1024u);
+                }
+                // a row that does not exist starts from the sentinel behind the -lse/scale array: P = 0 exactly
+                int row = row0 + l32;
+                const bool dead = row >= n_rows;
+                row = row < n_rows ? row : n_rows - 1;
+                const int64_t idx = (int64_t)h * p.total_q + q_base + row;
+                const float* src = hf == 0 ? p.neg_lse_s + (dead ? (int64_t)p.Hq * p.total_q : idx) : p.neg_delta + idx;
+                copy4_global_to_lds_at(src, unit + 4u * (uint32_t)SM::TILE);
+            }
+        }
+        wait_vmem_loads();
+        lds_barrier();
+
+        auto unit_ptr = [&](int u) { return units + (size_t)u * SM::UNIT_BYTES; };
+        // ---- the keys, 32 per wave and pass
+        for (int k0 = wave * 32; k0 < LK; k0 += NW * 32) {
+            const int kw = k0;
+            const bool key_live = kw + l32 < LK;
+            const bool ragged = kw + 32 > LK;
+            bf16x8 kf[NKS], vf[NKS];
+            {
+                const int key = key_live ? kw + l32 : LK - 1;
+                const int64_t off = ((kv_base + key) * p.Hkv + g) * D + 8 * hf;
+#pragma unroll
+                for (int ks = 0; ks < NKS; ks++) {
+                    kf[ks] = *(const bf16x8*)((const __bf16*)p.k + off + ks * 16);
+                    vf[ks] = *(const bf16x8*)((const __bf16*)p.v + off + ks * 16);
+                }
+            }
+            floatx16 dK[NDB], dV[NDB];  // [key (registers)][d (lanes)]
+#pragma unroll
+            for (int db = 0; db < NDB; db++)
+#pragma unroll
+                for (int v = 0; v < 16; v++) {
+                    dK[db][v] = 0.f;
+                    dV[db][v] = 0.f;
+                }
+            auto load_operands = [&](const unsigned char* ubase, Operands& o) {
+                const __bf16* Qs = (const __bf16*)ubase;
+                const __bf16* dOs = Qs + SM::TILE;
+                const float* ss = (const float*)(dOs + SM::TILE);
+#pragma unroll
+                for (int ks = 0; ks < NKS; ks++) {
+                    o.qa[ks] = *(const bf16x8*)(Qs + nat_off[ks]);
+                    o.da[ks] = *(const bf16x8*)(dOs + nat_off[ks]);
+                }
+                // accumulators start from -lse/scale and -delta of their rows (registers 4j..4j+3 hold rows 8j+4hf .. +3)
+                floatx4 l4[4], d4[4];
+#pragma unroll
+                for (int j = 0; j < 4; j++) {
+                    l4[j] = *(const floatx4*)(ss + 8 * j + 4 * hf);
+                    d4[j] = *(const floatx4*)(ss + 32 + 8 * j + 4 * hf);
+                }
+                o.S = __builtin_shufflevector(__builtin_shufflevector(l4[0], l4[1], 0, 1, 2, 3, 4, 5, 6, 7),
+                                              __builtin_shufflevector(l4[2], l4[3], 0, 1, 2, 3, 4, 5, 6, 7), 0, 1, 2, 3, 4, 5, 6,
+                                              7, 8, 9, 10, 11, 12, 13, 14, 15);
+                o.dP = __builtin_shufflevector(__builtin_shufflevector(d4[0], d4[1], 0, 1, 2, 3, 4, 5, 6, 7),
+                                               __builtin_shufflevector(d4[2], d4[3], 0, 1, 2, 3, 4, 5, 6, 7), 0, 1, 2, 3, 4, 5, 6,
+                                               7, 8, 9, 10, 11, 12, 13, 14, 15);
+            };
+            auto scores = [&](Operands& o) {
+#pragma unroll
+                for (int ks = 0; ks < NKS; ks++) {
+                    o.S = mfma32(o.qa[ks], kf[ks], o.S);     // S - lse/scale
+                    o.dP = mfma32(o.da[ks], vf[ks], o.dP);   // dP - delta
+                }
+            };
+            auto load_transposed = [&](const unsigned char* ubase, Transposed& f) {
+                const __bf16* Qs = (const __bf16*)ubase;
+                const __bf16* dOs = Qs + SM::TILE;
+#pragma unroll
+                for (int db = 0; db < NDB; db++)
+#pragma unroll
+                    for (int s2 = 0; s2 < 2; s2++) {
+                        f.dot[db][s2] = lds_read_tr_pair(dOs + tr_lo[db] + 16 * s2 * D, dOs + tr_hi[db] + 16 * s2 * D);
+                        f.qt[db][s2] = lds_read_tr_pair(Qs + tr_lo[db] + 16 * s2 * D, Qs + tr_hi[db] + 16 * s2 * D);
+                    }
+            };
+            auto weights = [&](const Operands& o, Weights& wt) {
+#pragma unroll
+                for (int v = 0; v < 16; v++) {
+                    float pw = fast_exp2(o.S[v] * c2);
+                    if (ragged) pw = key_live ? pw : 0.f;  // keys past the history carry no weight
+                    wt.pb[v / 8][v % 8] = (__bf16)pw;
+                    wt.dsb[v / 8][v % 8] = (__bf16)(pw * o.dP[v]);
+                }
+            };
+            // dV[key][d] += P^T[key][row] dO[row][d];  dK[key][d] += dS^T[key][row] Q[row][d]
+            auto accumulate = [&](const Weights& wt, const Transposed& f) {
+#pragma unroll
+                for (int db = 0; db < NDB; db++)
+#pragma unroll
+                    for (int s2 = 0; s2 < 2; s2++) {
+                        dV[db] = mfma32(wt.pb[s2], f.dot[db][s2], dV[db]);
+                        dK[db] = mfma32(wt.dsb[s2], f.qt[db][s2], dK[db]);
+                    }
+            };
+            // one unit after the other: the other two waves of the SIMD fill what this one waits for
+            {
+                Operands cur;
+                Transposed f;
+                Weights wt;
+                for (int u = 0; u < n_units; u++) {
+                    load_operands(unit_ptr(u), cur);
+                    scores(cur);
+                    load_transposed(unit_ptr(u), f);
+                    weights(cur, wt);
+                    accumulate(wt, f);
+                }
+            }
+            // write the wave's 32 key rows: lanes cover 32 consecutive d
+            __bf16* dkg = (__bf16*)p.dk;
+            __bf16* dvg = (__bf16*)p.dv;
+#pragma unroll
+            for (int v = 0; v < 16; v++) {
+                const int key = kw + 8 * (v / 4) + 4 * hf + (v % 4);
+                if (key < LK) {
+                    const int64_t off = ((kv_base + key) * p.Hkv + g) * D + l32;
+#pragma unroll
+                    for (int db = 0; db < NDB; db++) {
+                        dkg[off + db * 32] = (__bf16)(dK[db][v] * p.scale);
+                        dvg[off + db * 32] = (__bf16)dV[db][v];
+                    }
+                }
+            }
+        }
+    };  // process
+
+    // persistent workgroup, as in bwd_dkdv_kernel
+    const int xcd = blockIdx.x % N_XCD;
+    unsigned taken = 0;
+    if (tid == 0) taken = queue_take_ahead(p.queue, xcd);
+    for (;;) {
+        if (tid == 0) s_item = queue_resolve(p.queue, xcd, taken, per_xcd);
+        __syncthreads();
+        const int id = s_item;
+        if (id < 0) break;
+        if (tid == 0) taken = queue_take_ahead(p.queue, xcd);
+        process((unsigned)id);
+        __syncthreads();  // the staged units and s_item are free again
+    }
+}
+
 int gcd_i(int a, int b) { return b == 0 ? a : gcd_i(b, a % b); }
 
 template <int D, int RB, int NW>
@@ -828,8 +1065,34 @@ hipError_t launch_dkdv_as(const Params& p, hipStream_t s) {
     return hipGetLastError();
 }
 
+// Users with few query rows against long histories (see bwd_dkdv_resident_kernel): do the host-known bounds allow it,
+// and are there enough (user, kv head) items to give every compute unit one?  (A workgroup walks all keys of its item
+// by itself: with fewer items the key tiles of the streaming kernel spread better.)
+template <int D>
+bool few_rows_per_user(const Params& p) {
+    const int64_t max_units = ((max_query_rows(p) + 31) / 32) * (p.Hq / p.Hkv);
+    return D == 64 && !p.rt_len && !p.pointwise && max_units > 0 && max_units <= DkdvResident<D, 12>::MAX_UNITS &&
+           max_lead_keys(p) >= 512 && (int64_t)p.batch * p.Hkv >= 256;
+}
+
+template <int D>
+hipError_t launch_dkdv_resident(const Params& p, hipStream_t s) {
+    constexpr int NW = 12;
+    const int64_t n_items = work_grid((int64_t)p.batch * p.Hkv, 1);
+    if (n_items >= (1ll << 31)) return hipErrorInvalidValue;
+    const int64_t resident = resident_workgroups<bwd_dkdv_resident_kernel<D, NW>>(NW * 64);
+    Params pk = p;
+    pk.queue = p.queue + QUEUE_DKDV * N_XCD;
+    hipLaunchKernelGGL((bwd_dkdv_resident_kernel<D, NW>), dim3((unsigned)(n_items < resident ? n_items : resident)), dim3(NW * 64),
+                       0, s, pk, (unsigned)(n_items / N_XCD));
+    return hipGetLastError();
+}
+
 template <int D, int NW>
 hipError_t launch_dkdv(const Params& p, hipStream_t s) {
+    if constexpr (D == 64) {
+        if (few_rows_per_user<D>(p)) return launch_dkdv_resident<D>(p, s);
+    }
     if (p.pointwise) return p.rt_len ? launch_dkdv_as<D, NW, true, true>(p, s) : launch_dkdv_as<D, NW, false, true>(p, s);
     return p.rt_len ? launch_dkdv_as<D, NW, true>(p, s) : launch_dkdv_as<D, NW, false>(p, s);
 }

@@ -131,6 +131,13 @@ def test_split_forward_stays_inside_its_buffers(layer, rt):
     settle(guards, results)
 
 
+def test_few_rows_long_histories_stay_inside_their_buffers():
+    # enough (user, kv head) items of a target-only layer for the dK/dV launch that keeps a user's query rows in LDS
+    hist, tgts = [600, 0, 513, 1030, 64, 257, 255, 256, 0] * 15, [128, 5, 0, 33, 70, 1, 96, 2, 0] * 15
+    run_attention(case_of(TARGET, 8, 2, 64, "bf16", hist=hist, tgts=tgts))
+    run_attention(case_of(TARGET, 16, 4, 64, "bf16", hist=hist, tgts=tgts))
+
+
 def test_the_last_user_ends_exactly_at_the_end_of_the_buffers():
     # one user whose rows end a row tile / key tile early by one, and one that fills them exactly
     for hist, tgts in (([127], [1]), ([128], [64]), ([129], [63]), ([255, 1], [1, 0])):

@@ -83,6 +83,19 @@ def test_bf16_edge_cases_backward(layer, Hq, Hkv, d):
     check_case(c, with_bwd=True)
 
 
+@pytest.mark.parametrize("Hq,Hkv", [(8, 2), (4, 4), (3, 1), (16, 4)])
+def test_bf16_few_query_rows_against_long_histories(Hq, Hkv):
+    # A target-only layer with at most 128 candidates per user against histories of hundreds of keys: the dK/dV pass
+    # keeps all query rows of a (user, kv head) in LDS and walks the keys (the launch is chosen from the bounds of the
+    # batch).  Histories around the 256-key stride of a workgroup pass, users without candidates, without history,
+    # without both; odd and even numbers of (head, row block) units, up to the sixteen the kernel holds.
+    # (That launch also wants a (user, kv head) item for every compute unit: 135 users; with one kv head the batch has
+    # too few and stays with the kernel that streams the rows.)
+    hist, tgts = [600, 0, 513, 1030, 64, 257, 255, 256, 0] * 15, [128, 5, 0, 33, 70, 1, 96, 2, 0] * 15
+    c = custom(f"bf16_few_rows_{Hq}_{Hkv}", TARGET, hist, tgts, Hq, Hkv, 64, "bf16")
+    check_case(c, with_bwd=True)
+
+
 def test_c2_bf16_backward_full_batch():
     check_case(inputs.make_case(inputs.CONFIGS["C2"]), with_bwd=True)
 
