@@ -632,7 +632,7 @@ __global__ __launch_bounds__(NW * 64, D > 64 ? 1 : 2) void bwd_dkdv_kernel(Param
             for (int v = 0; v < 16; v++) {
                 const float sg = pw_sigmoid(o.S[v], -c2);
                 const float x = o.S[v] * p.scale;
-                float pw = pw_silu(x, sg), sp = pw_silu_prime(x, sg);
+                float pw = pw_silu(x, sg), sp = pw_silu_prime_of(pw, sg);
                 if constexpr (MASKED && RT) {
                     const int key = kw + l32;
                     const bool vis = key < limv[v] || (key_live && self_row == 8 * (v / 4) + 4 * hf + (v % 4));

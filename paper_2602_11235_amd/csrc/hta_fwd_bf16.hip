@@ -36,7 +36,7 @@ constexpr float RESCALE_SLACK = 8.f;  // log2 units a row's logits may exceed it
 // epilogue exactly like a target row.
 //
 // PW: the pointwise reading of phi2 -- weights norm * silu(scale s) on the same tiles and mask: no running maximum, no
-// row sum, no lse; the accumulator is scaled by norm at the store.
+// row sum, no lse; the accumulator holds sum_k s sigma(scale s) v and is scaled by norm * scale at the store.
 template <int D, int RB, bool RT, bool PW>
 struct FwdRows {
     static constexpr int NKS = D / 16, NDB = D / 32;
@@ -136,7 +136,7 @@ struct FwdRows {
             for (int rb = 0; rb < RB; rb++)
 #pragma unroll
                 for (int v = 0; v < 16; v++)
-                    pf[rb][v / 8][v % 8] = (__bf16)pw_silu(S[rb][v] * scale, pw_sigmoid(S[rb][v], neg_c2));
+                    pf[rb][v / 8][v % 8] = (__bf16)pw_silu(S[rb][v], pw_sigmoid(S[rb][v], neg_c2));  // s sigma(scale s): `scale` waits for the store
         } else {
             // Online softmax, one query row per lane (two lanes, 32 apart, share a row).  The reference m[rb]
             // of a row only has to bound its logits from above up to a modest factor: weights are exp2(s - m), sums
@@ -226,7 +226,7 @@ struct FwdRows {
                 dot += other_half(dot);
                 float alpha = 1.f, ps;
                 if constexpr (PW) {
-                    ps = pw_silu(dot * scale, pw_sigmoid(dot, neg_c2));
+                    ps = pw_silu(dot, pw_sigmoid(dot, neg_c2));
                 } else {
                     const float s2 = dot * c2;
                     const float m_new = fmaxf(m[rb], s2);
@@ -258,7 +258,7 @@ struct FwdRows {
             const bool live = row < n_rows;
             const float lt = l[rb] + other_half(l[rb]);
             if (live && SPLIT) {
-                const float inv = PW ? p.norm : (lt > 0.f ? 1.f / lt : 0.f);
+                const float inv = PW ? p.norm * scale : (lt > 0.f ? 1.f / lt : 0.f);
                 float* op = p.o_part + (((int64_t)split * p.total_q + q_base + row) * p.Hq + h) * D;
 #pragma unroll
                 for (int db = 0; db < NDB; db++)
@@ -273,7 +273,7 @@ struct FwdRows {
                     p.lse_part[((int64_t)split * p.Hq + h) * p.total_q + q_base + row] =
                         lt > 0.f ? (m[rb] + __builtin_amdgcn_logf(lt)) * LN2 : -INFINITY;
             } else if (live) {
-                const float inv = PW ? p.norm : 1.f / lt;
+                const float inv = PW ? p.norm * scale : 1.f / lt;
                 __bf16* op = (__bf16*)p.out + ((q_base + row) * p.Hq + h) * D;
 #pragma unroll
                 for (int db = 0; db < NDB; db++)

@@ -54,6 +54,8 @@ constexpr float PW_MASKED = -1e30f;
 __device__ inline float pw_sigmoid(float s, float neg_c2) { return __builtin_amdgcn_rcpf(1.f + fast_exp2(s * neg_c2)); }
 __device__ inline float pw_silu(float x, float sg) { return x * sg; }
 __device__ inline float pw_silu_prime(float x, float sg) { return fmaf(sg, x * (1.f - sg), sg); }
+// the same from silu(x) = x sigma, where that is at hand: silu'(x) = sigma + silu(x) (1 - sigma)
+__device__ inline float pw_silu_prime_of(float silu, float sg) { return fmaf(silu, 1.f - sg, sg); }
 
 // value held by the lane 32 positions away (the other half of the wave); v_permlane32_swap is a VALU
 // exchange of the upper half of its first operand with the lower half of its second
