@@ -28,8 +28,9 @@
  * DEVICE pointer; `stream` is a hipStream_t passed as void* (NULL = the default stream).  The caller
  * owns all buffers.  The functions declared in this header never allocate or free device memory, never copy
  * to the host and never synchronise: a call validates its scalar arguments on the host, enqueues kernels on
- * `stream` and returns.  (The optional instrumentation of mtfm_hta_timing.h is separate and does block.)  Device-resident arrays are not validated (that would need a device-to-host copy);
- * they must satisfy the layout above, and hist_len[b] <= max_hist, n_targets[b] <= max_targets.
+ * `stream` and returns.  (The optional instrumentation of mtfm_hta_timing.h is separate and does block.)
+ * Device-resident arrays are not validated (that would need a device-to-host copy); they must satisfy the
+ * layout above, and hist_len[b] <= max_hist, n_targets[b] <= max_targets.
  *
  * Errors.  Every entry point returning int returns an mtfm_hta_status; on a non-zero status nothing
  * has been enqueued (except MTFM_HTA_ERR_LAUNCH, reported by the runtime after an enqueue), and
@@ -139,9 +140,10 @@ MTFM_HTA_API int mtfm_hta_fwd_static(const void* q, const void* k, const void* v
  *   dk, dv        out [total_kv][Hkv][head_dim] fully overwritten (in a target layer history rows receive the
  *                 gradient of every target query, target rows that of their own query)
  * `out` and `lse` must be what mtfm_hta_fwd produced for the same inputs.  Remaining arguments as in
- * mtfm_hta_fwd.  The bf16 path needs a workspace (mtfm_hta_workspace_bytes with is_bwd = 1) and is
- * bitwise reproducible; the fp32 debug path sums dk/dv with float32 atomics, so it is reproducible to
- * rounding only.
+ * mtfm_hta_fwd.  batch == 0 or total_kv == 0 is a successful no-op; with total_q == 0 (a target layer whose
+ * users have no candidate) the row-shaped tensors are empty and may be null, and dk = dv = 0 is written.
+ * The bf16 path needs a workspace (mtfm_hta_workspace_bytes with is_bwd = 1) and is bitwise reproducible;
+ * the fp32 debug path sums dk/dv with float32 atomics, so it is reproducible to rounding only.
  */
 MTFM_HTA_API int mtfm_hta_bwd(const void* dout, const void* q, const void* k, const void* v, const void* out,
                  const float* lse, void* dq, void* dk, void* dv, const int32_t* q_offsets,

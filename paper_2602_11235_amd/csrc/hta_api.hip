@@ -374,8 +374,11 @@ static int bwd_impl(const void* dout, const void* q, const void* k, const void* 
     if (pointwise && (!(norm > 0.f) || !std::isfinite(norm)))
         return fail(MTFM_HTA_ERR_INVALID_ARG, "norm must be positive and finite");
     if (batch == 0 || total_kv == 0) return MTFM_HTA_OK;
-    if (!dout || !q || !k || !v || (!pointwise && (!out || !lse)) || !dq || !dk || !dv || !q_offsets || !kv_offsets ||
-        !hist_len || !n_targets)
+    // a target layer whose users have no candidate at all has no query row (total_q == 0): the row-shaped tensors are
+    // empty then and may be null; dk = dv = 0 is still written
+    const bool no_rows = total_q == 0;
+    if ((!no_rows && (!dout || !q || (!pointwise && (!out || !lse)) || !dq)) || !k || !v || !dk || !dv || !q_offsets ||
+        !kv_offsets || !hist_len || !n_targets)
         return fail(MTFM_HTA_ERR_INVALID_ARG, "null pointer argument");
     if (misaligned(dout) || misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out) || misaligned(dq) ||
         misaligned(dk) || misaligned(dv))

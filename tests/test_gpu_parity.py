@@ -96,6 +96,23 @@ def test_bf16_few_query_rows_against_long_histories(Hq, Hkv):
     check_case(c, with_bwd=True)
 
 
+@pytest.mark.parametrize("dtype,d", [("bf16", 64), ("bf16", 16), ("fp32", 24)])
+def test_target_layer_without_any_candidate(dtype, d):
+    # no user of the batch has a target: there is no query row (empty row-shaped tensors, null pointers at the
+    # boundary), the forward call has nothing to do and the backward call still has to write dk = dv = 0
+    c = custom(f"no_candidates_{dtype}_{d}", TARGET, [300, 0, 64, 129], [0, 0, 0, 0], 8, 2, d, dtype)
+    assert c.total_q == 0 and c.total_kv == 493
+    b = device_batch(c)
+    b.forward()
+    b.prepare_backward()
+    b.dk.fill_(float("nan"))
+    b.dv.fill_(float("nan"))
+    dq, dk, dv = b.backward(to_torch(c.dout, dtype))
+    torch.cuda.synchronize()
+    assert dq.shape[0] == 0
+    assert torch.equal(dk, torch.zeros_like(dk)) and torch.equal(dv, torch.zeros_like(dv))
+
+
 def test_c2_bf16_backward_full_batch():
     check_case(inputs.make_case(inputs.CONFIGS["C2"]), with_bwd=True)
 
