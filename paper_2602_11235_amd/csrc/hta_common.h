@@ -65,6 +65,9 @@ hipError_t launch_fwd_fp32(const Params& p, hipStream_t s);
 hipError_t launch_bwd_fp32(const Params& p, hipStream_t s);
 hipError_t launch_fwd_bf16(const Params& p, hipStream_t s);
 hipError_t launch_bwd_bf16(const Params& p, hipStream_t s);
+// the two launches of launch_bwd_bf16 that live in translation units of their own (other compiler options)
+hipError_t launch_bwd_dq_bf16(const Params& p, hipStream_t s);       // dQ and the self-key blocks, every head_dim
+hipError_t launch_bwd_dkdv128_bf16(const Params& p, hipStream_t s);  // dK/dV at head_dim 128, softmax weights, no real-time tokens
 bool bf16_supported(int32_t d, int32_t Hq, int32_t Hkv);
 // bf16 rows of 16 features <-> rows of 32 with a zero upper half ([n_rows][16] and [n_rows][32], 16-byte aligned): how
 // head_dim 16 rides the 32-wide matrix tiles
@@ -116,9 +119,10 @@ inline int64_t work_grid(int64_t n_groups, int64_t tpg) { return ((n_groups + N_
 // hands the workgroups of a grid to the shader engines in a fixed rotation, whatever each has left to do, so with items
 // of unequal length (jagged users) whole compute units run dry while others queue up: a fifth of the chip on the
 // paper's length mix.  Such a kernel launches only as many workgroups as the chip holds at once, and each takes work
-// item after work item from a counter (kernels with short items lose more to the hand-over than they gain): XCD x serves the ids x, x + 8, x + 16, ... (which keeps a group's tiles on one L2, as
-// above), in order, through counters[x]; a workgroup whose own XCD has nothing left helps the others.  The loop ends
-// for a workgroup once every counter has passed the end of its list, which every workgroup reaches.
+// item after work item from a counter (kernels with short items lose more to the hand-over than they gain): XCD x
+// serves the ids x, x + 8, x + 16, ... (which keeps a group's tiles on one L2, as above), in order, through counters[x];
+// a workgroup whose own XCD has nothing left helps the others.  The loop ends for a workgroup once every counter has
+// passed the end of its list, which every workgroup reaches.
 //   thread 0:  take the next slot of the own XCD in advance (one atomic, its latency hidden behind an item) ...
 __device__ inline unsigned queue_take_ahead(int32_t* counters, int xcd) { return atomicAdd((unsigned*)&counters[xcd], 1u); }
 //   ... and turn it into a work id, or -1 when all lists are exhausted
