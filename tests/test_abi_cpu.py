@@ -90,6 +90,28 @@ def test_backward_reports_missing_workspace():
     assert rc == hta.ERR_WORKSPACE and "workspace" in hta.mtfm_hta_last_error()
 
 
+def test_backward_without_query_rows_takes_null_row_tensors():
+    # a target layer whose users have no candidate: total_q = 0, the row-shaped tensors are empty.  The call gets past
+    # its pointer checks (it stops at the missing workspace here); with a key/value tensor missing it does not.
+    lib = hta.load_library()
+    row, kv, idx = [None] * 2, [4096] * 2, [4096] * 4
+    rc = lib.mtfm_hta_bwd(None, None, *kv, None, None, None, *kv, *idx, 2, 0, 10, 8, 0, 8, 2, 64, 0.125, hta.BF16,
+                          hta.LAYER_TARGET, None, 0, None)
+    assert rc == hta.ERR_WORKSPACE, hta.mtfm_hta_last_error()
+    rc = lib.mtfm_hta_bwd(None, None, None, 4096, None, None, None, *kv, *idx, 2, 0, 10, 8, 0, 8, 2, 64, 0.125, hta.BF16,
+                          hta.LAYER_TARGET, None, 0, None)
+    assert rc == hta.ERR_INVALID_ARG and "null" in hta.mtfm_hta_last_error()
+    rc = lib.mtfm_hta_bwd(None, None, *kv, None, None, None, *kv, *idx, 2, 5, 10, 8, 5, 8, 2, 64, 0.125, hta.BF16,
+                          hta.LAYER_TARGET, None, 0, None)
+    assert rc == hta.ERR_INVALID_ARG and "null" in hta.mtfm_hta_last_error()
+
+
+def test_per_file_compiler_options_name_existing_sources():
+    from paper_2602_11235_amd import build
+    names = {os.path.basename(s) for s in build.sources()}
+    assert set(build.FILE_FLAGS) <= names, set(build.FILE_FLAGS) - names
+
+
 def test_empty_batch_is_ok_without_a_device():
     lib = hta.load_library()
     assert lib.mtfm_hta_fwd(None, None, None, None, None, None, None, None, None, 0, 0, 0, 0, 0, 8, 2, 64, 0.125,
