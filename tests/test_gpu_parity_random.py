@@ -10,6 +10,7 @@ import pytest
 
 from paper_2602_11235_amd import inputs
 from tests.hta_testlib import check_case, close_on_row_scale, say
+from tests.test_gpu_parity_pointwise import check as check_pointwise
 
 pytestmark = pytest.mark.gpu
 FULL, TARGET = inputs.LAYER_FULL, inputs.LAYER_TARGET
@@ -52,6 +53,17 @@ def test_random_shapes_with_realtime_tokens(seed):
     cfg = inputs.custom_config(f"random_rt_{seed}", layer, hist, tgts, Hq, Hkv, d, dtype="bf16", std=0.3,
                                seed=700 + seed, rt_len=rt)
     check_case(inputs.make_case(cfg), with_bwd=True, compare=close_on_row_scale)
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_shapes_with_pointwise_weights(seed):
+    # even seeds without, odd seeds with real-time tokens; norm = 1, so that the results are of order one or larger and
+    # the relative part of the bound is the one that binds
+    layer, hist, tgts, Hq, Hkv, d, rt = draw_shape(200 + seed, seed % 2 == 1)
+    say(f"  seed {seed}: layer {layer} heads {Hq}/{Hkv} d {d} hist {list(hist)} rt {rt} targets {list(tgts)}")
+    cfg = inputs.custom_config(f"random_pw_{seed}", layer, hist, tgts, Hq, Hkv, d, dtype="bf16", std=0.3,
+                               seed=800 + seed, rt_len=rt)
+    check_pointwise(inputs.make_case(cfg), norm=1.0, compare=close_on_row_scale)
 
 
 def test_random_fp32_shape():
